@@ -1,0 +1,152 @@
+/*
+ * svdq.h -- C ABI of the MI355X (gfx950) W4A4 SVDQuant-style linear layer.
+ *
+ * The layer (paper Sec. III-B eq. 7 and Sec. III-C eq. 11, with the uniform
+ * quantiser of Sec. III-A eq. 3-4 and the clipping threshold of eq. 8-9):
+ *
+ *   x^ = x / lambda                                   smoothing, eq. 5
+ *   Q_A(x^) : per token, per 64-group: a = max|x^|, s = rho*a/7,
+ *             q = clip(round_half_even(x^/s), -8, 7)   eq. 3, 8, 9
+ *   y  = sum_g (sum_{k in g} q[m,k] qw[n,k]) s[m,g] sw[g,n]     4-bit branch
+ *      + (x^ L1) L2                                     low-rank branch, eq. 7
+ *      + b
+ *
+ * rho is the clipping ratio the paper looks up per (expert, layer, timestep
+ * bin); lambda, L1, L2, the int4 residual codes qw and their scales sw come
+ * from offline calibration (smoothing, SVD split, GPTQ) and are inputs here.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller, valid on the
+ *     current HIP device, 16-byte aligned, not aliasing any output.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it; nothing synchronises; the library keeps no state
+ *     besides a cached device-architecture check, and allocates nothing.
+ *   - Return value: SVDQ_OK or a negative svdq_status.  Arguments are checked on
+ *     the host BEFORE any launch, so an error means nothing was enqueued.
+ *     M == 0 is a successful no-op.  NaN/Inf inputs give unspecified outputs.
+ *   - Row-major everywhere.  bf16 = upper half of an IEEE binary32.
+ *   - Canonical packed int4: byte j of a row holds code 2j in its low nibble
+ *     and code 2j+1 in its high nibble, 4-bit two's complement.
+ *   - Group size is 64 along K; K % 64 == 0.
+ */
+#ifndef SVDQ_H
+#define SVDQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SVDQ_OK = 0,
+    SVDQ_ERR_INVALID_ARG = -1,        /* NULL required pointer, negative size, rho outside (0,1], bad enum */
+    SVDQ_ERR_UNSUPPORTED_SHAPE = -2,  /* K % 64, N % 128, r not in {0,16,32}, ld too small or misaligned */
+    SVDQ_ERR_UNSUPPORTED_ARCH = -3,   /* current device is not gfx950 */
+    SVDQ_ERR_HIP = -4                 /* a HIP runtime call or launch failed */
+} svdq_status;
+
+enum { SVDQ_GROUP = 64, SVDQ_N_TILE = 128, SVDQ_MAX_RANK = 32 };
+enum { SVDQ_OUT_BF16 = 0, SVDQ_OUT_F32 = 1 };
+
+const char* svdq_status_string(int status);
+
+/* ABI version; bumped when a signature or a packed layout changes. */
+int svdq_version(void);
+
+/*
+ * Host helper for Sec. III-C: map a denoising step to its timestep bin and
+ * return that bin's clipping ratio.  `table` is a HOST array of nbins ratios of
+ * one expert; the expert covers steps [step0, step0 + nsteps_expert); bins are
+ * uniform over that range: bin = floor((step - step0) * nbins / nsteps_expert).
+ * Returns NaN for a NULL table, nbins <= 0, nsteps_expert <= 0 or a step outside
+ * the range.
+ */
+float svdq_alpha_lookup(const float* table, int nbins, int step, int step0, int nsteps_expert);
+
+/*
+ * One-time, offline: fold the smoothing vector into the low-rank down factor
+ * and lay it out for the quantise kernel.  Stores rn(inv_lambda[k] * L1[k,j])
+ * split into two bf16 pieces (hi + lo, 16 significant bits) in matrix-core
+ * operand order, zero-padded to 32 columns.
+ *   L1_bf16     [K, r] bf16, r in {16, 32}
+ *   inv_lambda  [K] binary32, the caller's RN(1/lambda[k])        (eq. 5)
+ *   l1_packed   out, svdq_packed_l1_bytes(K) bytes
+ */
+size_t svdq_packed_l1_bytes(int K);
+int svdq_pack_lowrank_down(const void* L1_bf16, const float* inv_lambda, int K, int r,
+                           void* l1_packed, void* stream);
+
+/*
+ * Kernel (a): ONE pass over x that smooths (eq. 5), takes the per-token
+ * per-64-group absmax, derives the clipped scale (eq. 8-9), rounds and packs
+ * int4 codes (eq. 3) and computes the low-rank down-projection h = x^ L1 on
+ * the un-quantised x^ (eq. 7).
+ *   x_bf16      [M, ldx] bf16, first K columns used; ldx >= K, ldx % 8 == 0
+ *   inv_lambda  [K] binary32
+ *   rho         clipping ratio in (0, 1]
+ *   l1_packed   from svdq_pack_lowrank_down, or NULL to skip h (then r must be 0)
+ *   qx          out [M, K/2] canonical packed codes
+ *   sx          out [M, K/64] binary32 scales; a group whose scale would not be a
+ *               normal number gets scale 0 and codes 0
+ *   h           out [M, r] binary32 (ignored when l1_packed == NULL)
+ * Bit-exact contract: x^ = x * inv_lambda, a = max|x^|, s = (rho*a)/7,
+ * q = clip(rne(x^ * (1/s))), each a single IEEE binary32 operation.
+ */
+int svdq_quantize_act(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                      const void* l1_packed, int64_t M, int K, int r,
+                      uint8_t* qx, float* sx, float* h, void* stream);
+
+/*
+ * One-time, offline: canonical residual codes + scales -> kernel-private layout.
+ *   qw        [N, K/2] canonical packed int4 codes of the residual R (eq. 6)
+ *   sw        [K/64, N] binary32 scales
+ *   w_packed  out, svdq_packed_weight_bytes(N, K) bytes (codes stay 4-bit)
+ * N % 128 == 0.
+ */
+size_t svdq_packed_weight_bytes(int N, int K);
+int svdq_pack_weight(const uint8_t* qw, const float* sw, int N, int K, void* w_packed, void* stream);
+
+/*
+ * Kernels (b)+(c): int4 x int4 GEMM on the int8 matrix cores with one int32
+ * accumulator per 64-group, binary32 dequantisation, then the fused epilogue
+ * y = main + h L2 + bias with one rounding to the output type.
+ *   qx, sx    as written by svdq_quantize_act
+ *   w_packed  from svdq_pack_weight
+ *   h         [M, r] binary32 and L2_bf16 [r, N] bf16, or both NULL with r == 0
+ *   bias      [N] binary32 or NULL
+ *   y         out [M, ldy]; bf16 (round-to-nearest-even) for SVDQ_OUT_BF16,
+ *             binary32 for SVDQ_OUT_F32 (the value before the bf16 rounding;
+ *             meant for tests); ldy >= N, ldy % 8 == 0
+ */
+int svdq_linear_w4a4(const uint8_t* qx, const float* sx, const void* w_packed,
+                     const float* h, const void* L2_bf16, const float* bias,
+                     int64_t M, int N, int K, int r,
+                     void* y, int64_t ldy, int out_dtype, void* stream);
+
+/*
+ * Un-fused low-rank branch of eq. 7, for callers that run the two halves
+ * separately and as a cross-check of the fused kernels.
+ *   mode 0:  h[M,r] = (x * inv_lambda) L1     x_bf16 [M,ldx], L1_bf16 [K,r] raw bf16
+ *            (uses x_bf16, ldx, inv_lambda, L_bf16 = L1, K, r, h as output)
+ *   mode 1:  y[M,ldy] (bf16, in/out) += h L2   L_bf16 = L2 [r,N]
+ *            (uses h as input, L_bf16 = L2, N, r, y_bf16, ldy)
+ * Unused arguments are ignored.  r in {16, 32}.
+ */
+int svdq_lowrank(int mode, const void* x_bf16, int64_t ldx, const float* inv_lambda,
+                 const void* L_bf16, int64_t M, int K, int N, int r,
+                 float* h, void* y_bf16, int64_t ldy, void* stream);
+
+/*
+ * Test hook: the int32 group accumulators acc[m,n,g] = sum_{k in g} q[m,k] qw[n,k]
+ * exactly as the GEMM kernel's matrix-core path forms them, for rows
+ * [m0, m0+mt) of an M-row problem:  acc out [mt, N, K/64] int32.
+ */
+int svdq_debug_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int N, int K,
+                         int64_t m0, int mt, int32_t* acc, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

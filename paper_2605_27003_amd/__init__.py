@@ -1,0 +1,13 @@
+"""MI355X-native W4A4 SVDQuant-style linear layer (gfx950 HIP kernels behind a C ABI).
+
+Thin Python binding over libsvdq.so: argument marshalling only.  Every step of
+the path (smoothing, absmax, int4 quantise/pack, low-rank down-projection,
+int4 GEMM with per-group dequantisation, low-rank up-projection, bias, bf16
+store) runs in the HIP kernels.  There is no CPU fallback: if the library is
+missing or the device is not gfx950 the calls raise.
+"""
+from .binding import (  # noqa: F401
+    SvdqError, alpha_lookup, debug_group_acc, linear_w4a4, load_library, lowrank,
+    pack_lowrank_down, pack_weight, packed_l1_bytes, packed_weight_bytes, quantize_act, version,
+    W4A4Linear,
+)

@@ -1,0 +1,194 @@
+"""ctypes binding of include/svdq.h for torch tensors (device memory and streams only)."""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsvdq.so")
+_lib = None
+
+OUT_BF16, OUT_F32 = 0, 1
+_vp, _i64, _i32, _f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+
+EXPORTS = {
+    "svdq_status_string": (ctypes.c_char_p, [_i32]),
+    "svdq_version": (_i32, []),
+    "svdq_alpha_lookup": (_f32, [_vp, _i32, _i32, _i32, _i32]),
+    "svdq_packed_l1_bytes": (ctypes.c_size_t, [_i32]),
+    "svdq_pack_lowrank_down": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
+    "svdq_quantize_act": (_i32, [_vp, _i64, _vp, _f32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "svdq_packed_weight_bytes": (ctypes.c_size_t, [_i32, _i32]),
+    "svdq_pack_weight": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
+    "svdq_linear_w4a4": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _i32, _vp]),
+    "svdq_lowrank": (_i32, [_i32, _vp, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _i64, _vp]),
+    "svdq_debug_group_acc": (_i32, [_vp, _vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp]),
+}
+
+
+class SvdqError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {load_library().svdq_status_string(status).decode()} ({status})")
+
+
+def load_library(build_if_missing=True):
+    """Load libsvdq.so (built in-tree by paper_2605_27003_amd/build.py); never falls back to anything else."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            if not build_if_missing:
+                raise FileNotFoundError(_LIB_PATH)
+            from . import build as _build
+            _build.build(force=True)
+        lib = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise SvdqError(rc, where)
+
+
+def version():
+    return int(load_library().svdq_version())
+
+
+def alpha_lookup(table, step, step0, nsteps_expert):
+    arr = (ctypes.c_float * len(table))(*table)
+    return float(load_library().svdq_alpha_lookup(ctypes.cast(arr, _vp), len(table), step, step0, nsteps_expert))
+
+
+def packed_l1_bytes(K):
+    return int(load_library().svdq_packed_l1_bytes(K))
+
+
+def packed_weight_bytes(N, K):
+    return int(load_library().svdq_packed_weight_bytes(N, K))
+
+
+def pack_lowrank_down(L1_bf16, inv_lambda):
+    """L1 [K,r] bf16, inv_lambda [K] f32 (device) -> opaque uint8 tensor for quantize_act."""
+    K, r = L1_bf16.shape
+    out = torch.empty(packed_l1_bytes(K), dtype=torch.uint8, device=L1_bf16.device)
+    _check(load_library().svdq_pack_lowrank_down(_ptr(L1_bf16), _ptr(inv_lambda), K, r, _ptr(out), _stream()),
+           "svdq_pack_lowrank_down")
+    return out
+
+
+def pack_weight(qw, sw):
+    """qw [N,K/2] uint8 canonical codes, sw [K/64,N] f32 (device) -> opaque uint8 tensor for linear_w4a4."""
+    N, K2 = qw.shape
+    K = 2 * K2
+    out = torch.empty(packed_weight_bytes(N, K), dtype=torch.uint8, device=qw.device)
+    _check(load_library().svdq_pack_weight(_ptr(qw), _ptr(sw), N, K, _ptr(out), _stream()), "svdq_pack_weight")
+    return out
+
+
+def quantize_act(x_bf16, inv_lambda, rho, l1_packed=None, r=0, out=None):
+    """x [M,K] bf16 (row stride allowed) -> (qx [M,K/2] u8, sx [M,K/64] f32, h [M,r] f32 or None)."""
+    M, K = x_bf16.shape
+    assert x_bf16.dtype == torch.bfloat16 and x_bf16.stride(1) == 1
+    dev = x_bf16.device
+    if out is None:
+        qx = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+        sx = torch.empty((M, K // 64), dtype=torch.float32, device=dev)
+        h = torch.empty((M, r), dtype=torch.float32, device=dev) if l1_packed is not None else None
+    else:
+        qx, sx, h = out
+    ldx = x_bf16.stride(0) if M > 1 else K
+    _check(load_library().svdq_quantize_act(_ptr(x_bf16), ldx, _ptr(inv_lambda), float(rho), _ptr(l1_packed),
+                                           M, K, r if l1_packed is not None else 0,
+                                           _ptr(qx), _ptr(sx), _ptr(h), _stream()), "svdq_quantize_act")
+    return qx, sx, h
+
+
+def linear_w4a4(qx, sx, w_packed, N, h=None, L2_bf16=None, bias=None, out=None, out_dtype=torch.bfloat16):
+    """-> y [M,N] bf16 (or f32 when out_dtype is torch.float32: the value before the bf16 rounding)."""
+    M, K2 = qx.shape
+    K = 2 * K2
+    r = 0 if h is None else h.shape[1]
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=qx.device)
+    code = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
+    ldy = out.stride(0) if M > 1 else N
+    _check(load_library().svdq_linear_w4a4(_ptr(qx), _ptr(sx), _ptr(w_packed), _ptr(h), _ptr(L2_bf16), _ptr(bias),
+                                          M, N, K, r, _ptr(out), ldy, code, _stream()), "svdq_linear_w4a4")
+    return out
+
+
+def lowrank(mode, *, x_bf16=None, inv_lambda=None, L_bf16=None, h=None, y_bf16=None):
+    """mode 0: h = (x*inv_lambda) L1 (returns h); mode 1: y += h L2 in place (returns y)."""
+    lib = load_library()
+    if mode == 0:
+        M, K = x_bf16.shape
+        r = L_bf16.shape[1]
+        if h is None:
+            h = torch.empty((M, r), dtype=torch.float32, device=x_bf16.device)
+        ldx = x_bf16.stride(0) if M > 1 else K
+        _check(lib.svdq_lowrank(0, _ptr(x_bf16), ldx, _ptr(inv_lambda), _ptr(L_bf16), M, K, 0, r,
+                                _ptr(h), None, 0, _stream()), "svdq_lowrank")
+        return h
+    M, N = y_bf16.shape
+    r = L_bf16.shape[0]
+    ldy = y_bf16.stride(0) if M > 1 else N
+    _check(lib.svdq_lowrank(1, None, 0, None, _ptr(L_bf16), M, 0, N, r, _ptr(h), _ptr(y_bf16), ldy, _stream()),
+           "svdq_lowrank")
+    return y_bf16
+
+
+def debug_group_acc(qx, w_packed, N, m0, mt):
+    """int32 group accumulators of rows [m0, m0+mt) as the GEMM kernel forms them -> [mt, N, K/64]."""
+    M, K2 = qx.shape
+    K = 2 * K2
+    acc = torch.empty((mt, N, K // 64), dtype=torch.int32, device=qx.device)
+    _check(load_library().svdq_debug_group_acc(_ptr(qx), _ptr(w_packed), M, N, K, m0, mt, _ptr(acc), _stream()),
+           "svdq_debug_group_acc")
+    return acc
+
+
+class W4A4Linear:
+    """One quantised linear resident in HBM: packed weights and low-rank factors, reusable output buffers."""
+
+    def __init__(self, inv_lambda, L1_bf16, L2_bf16, qw, sw, bias):
+        self.N, self.K = qw.shape[0], qw.shape[1] * 2
+        self.r = 0 if L1_bf16 is None else L1_bf16.shape[1]
+        self.inv_lambda = inv_lambda
+        self.l1_packed = pack_lowrank_down(L1_bf16, inv_lambda) if self.r else None
+        self.L2 = L2_bf16 if self.r else None
+        self.w_packed = pack_weight(qw, sw)
+        self.bias = bias
+        self._bufs = None
+
+    def buffers(self, M, device):
+        if self._bufs is None or self._bufs[0].shape[0] != M:
+            qx = torch.empty((M, self.K // 2), dtype=torch.uint8, device=device)
+            sx = torch.empty((M, self.K // 64), dtype=torch.float32, device=device)
+            h = torch.empty((M, self.r), dtype=torch.float32, device=device) if self.r else None
+            y = torch.empty((M, self.N), dtype=torch.bfloat16, device=device)
+            self._bufs = (qx, sx, h, y)
+        return self._bufs
+
+    def quantize(self, x_bf16, rho):
+        qx, sx, h, _ = self.buffers(x_bf16.shape[0], x_bf16.device)
+        return quantize_act(x_bf16, self.inv_lambda, rho, self.l1_packed, self.r, out=(qx, sx, h))
+
+    def gemm(self, qx, sx, h):
+        y = self.buffers(qx.shape[0], qx.device)[3]
+        return linear_w4a4(qx, sx, self.w_packed, self.N, h, self.L2, self.bias, out=y)
+
+    def forward(self, x_bf16, rho):
+        qx, sx, h = self.quantize(x_bf16, rho)
+        return self.gemm(qx, sx, h)

@@ -1,0 +1,150 @@
+// C ABI of the library (declared in include/svdq.h): argument validation on
+// the host, architecture check, kernel launches.  No allocation, no
+// synchronisation.
+#include "svdq.h"
+
+#include <cmath>
+#include <cstring>
+
+#include "svdq_kernels.h"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// SVDQ_OK when the current device is gfx950; cached per device index.
+int check_arch() {
+    static int cached[64];                         // 0 unknown, 1 ok, 2 unsupported
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return SVDQ_ERR_HIP;
+    if (dev < 0 || dev >= 64) return SVDQ_ERR_HIP;
+    if (cached[dev] == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return SVDQ_ERR_HIP;
+        cached[dev] = (std::strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : 2;
+    }
+    return cached[dev] == 1 ? SVDQ_OK : SVDQ_ERR_UNSUPPORTED_ARCH;
+}
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? SVDQ_OK : SVDQ_ERR_HIP; }
+
+inline bool rank_ok(int r) { return r == 16 || r == 32; }
+
+}  // namespace
+
+extern "C" {
+
+const char* svdq_status_string(int status) {
+    switch (status) {
+        case SVDQ_OK: return "ok";
+        case SVDQ_ERR_INVALID_ARG: return "invalid argument";
+        case SVDQ_ERR_UNSUPPORTED_SHAPE: return "unsupported shape";
+        case SVDQ_ERR_UNSUPPORTED_ARCH: return "unsupported GPU architecture (gfx950 required)";
+        case SVDQ_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int svdq_version(void) { return 1; }
+
+float svdq_alpha_lookup(const float* table, int nbins, int step, int step0, int nsteps_expert) {
+    if (!table || nbins <= 0 || nsteps_expert <= 0) return NAN;
+    const long long rel = (long long)step - step0;
+    if (rel < 0 || rel >= nsteps_expert) return NAN;
+    return table[(rel * nbins) / nsteps_expert];
+}
+
+size_t svdq_packed_l1_bytes(int K) {
+    if (K <= 0 || K % SVDQ_GROUP) return 0;
+    return svdq::packed_l1_bytes(K);
+}
+
+int svdq_pack_lowrank_down(const void* L1_bf16, const float* inv_lambda, int K, int r,
+                           void* l1_packed, void* stream) {
+    if (!L1_bf16 || !inv_lambda || !l1_packed) return SVDQ_ERR_INVALID_ARG;
+    if (K <= 0 || K % SVDQ_GROUP || !rank_ok(r)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(l1_packed)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_pack_l1(L1_bf16, inv_lambda, K, r, l1_packed, (hipStream_t)stream));
+}
+
+int svdq_quantize_act(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                      const void* l1_packed, int64_t M, int K, int r,
+                      uint8_t* qx, float* sx, float* h, void* stream) {
+    if (!x_bf16 || !inv_lambda || !qx || !sx || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (!(rho > 0.0f) || !(rho <= 1.0f)) return SVDQ_ERR_INVALID_ARG;      // also rejects NaN
+    if (l1_packed ? (!h) : (r != 0)) return SVDQ_ERR_INVALID_ARG;
+    if (K <= 0 || K % SVDQ_GROUP || ldx < K || ldx % 8) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (l1_packed && !rank_ok(r)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(x_bf16) || !aligned16(inv_lambda) || !aligned16(qx) || !aligned16(sx) ||
+        !aligned16(l1_packed) || (l1_packed && !aligned16(h)))
+        return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_quantize(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, qx, sx, h,
+                                            (hipStream_t)stream));
+}
+
+size_t svdq_packed_weight_bytes(int N, int K) {
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE) return 0;
+    return svdq::packed_weight_bytes(N, K);
+}
+
+int svdq_pack_weight(const uint8_t* qw, const float* sw, int N, int K, void* w_packed, void* stream) {
+    if (!qw || !sw || !w_packed) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(qw) || !aligned16(sw) || !aligned16(w_packed)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_pack_weight(qw, sw, N, K, w_packed, (hipStream_t)stream));
+}
+
+int svdq_linear_w4a4(const uint8_t* qx, const float* sx, const void* w_packed,
+                     const float* h, const void* L2_bf16, const float* bias,
+                     int64_t M, int N, int K, int r,
+                     void* y, int64_t ldy, int out_dtype, void* stream) {
+    if (!qx || !sx || !w_packed || !y || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (out_dtype != SVDQ_OUT_BF16 && out_dtype != SVDQ_OUT_F32) return SVDQ_ERR_INVALID_ARG;
+    if (r == 0 ? (h || L2_bf16) : (!h || !L2_bf16)) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE || ldy < N || ldy % 8)
+        return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (r != 0 && !rank_ok(r)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(qx) || !aligned16(sx) || !aligned16(w_packed) || !aligned16(h) || !aligned16(L2_bf16) ||
+        !aligned16(bias) || !aligned16(y))
+        return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_linear(qx, sx, w_packed, h, L2_bf16, bias, M, N, K, r, y, ldy,
+                                          out_dtype == SVDQ_OUT_F32, (hipStream_t)stream));
+}
+
+int svdq_lowrank(int mode, const void* x_bf16, int64_t ldx, const float* inv_lambda,
+                 const void* L_bf16, int64_t M, int K, int N, int r,
+                 float* h, void* y_bf16, int64_t ldy, void* stream) {
+    if (mode != 0 && mode != 1) return SVDQ_ERR_INVALID_ARG;
+    if (!L_bf16 || !h || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (!rank_ok(r)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (mode == 0) {
+        if (!x_bf16 || !inv_lambda) return SVDQ_ERR_INVALID_ARG;
+        if (K <= 0 || ldx < K) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    } else {
+        if (!y_bf16) return SVDQ_ERR_INVALID_ARG;
+        if (N <= 0 || ldy < N) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    }
+    if (M == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    if (mode == 0)
+        return hip_status(svdq::launch_lowrank_down(x_bf16, ldx, inv_lambda, L_bf16, M, K, r, h, (hipStream_t)stream));
+    return hip_status(svdq::launch_lowrank_up(h, L_bf16, M, N, r, y_bf16, ldy, (hipStream_t)stream));
+}
+
+int svdq_debug_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int N, int K,
+                         int64_t m0, int mt, int32_t* acc, void* stream) {
+    if (!qx || !w_packed || !acc || M < 0 || m0 < 0 || mt < 0 || m0 + mt > M) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(qx) || !aligned16(w_packed)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (mt == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_group_acc(qx, w_packed, M, N, K, m0, mt, acc, (hipStream_t)stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,32 @@
+// Host-callable launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace svdq {
+
+// svdq_quantize.hip
+hipError_t launch_quantize(const void* x, int64_t ldx, const float* inv_lambda, float rho,
+                           const void* l1p, int64_t M, int K, int r,
+                           uint8_t* qx, float* sx, float* h, hipStream_t stream);
+hipError_t launch_pack_l1(const void* L1, const float* inv_lambda, int K, int r, void* out, hipStream_t stream);
+inline size_t packed_l1_bytes(int K) { return (size_t)(K / 64) * 4 * 2 * 64 * 16; }
+
+// svdq_gemm.hip
+size_t packed_weight_bytes(int N, int K);
+hipError_t launch_pack_weight(const uint8_t* qw, const float* sw, int N, int K, void* out, hipStream_t stream);
+hipError_t launch_linear(const uint8_t* qx, const float* sx, const void* w_packed,
+                         const float* h, const void* L2, const float* bias,
+                         int64_t M, int N, int K, int r, void* y, int64_t ldy, int out_f32,
+                         hipStream_t stream);
+hipError_t launch_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int N, int K,
+                            int64_t m0, int mt, int32_t* acc, hipStream_t stream);
+
+// svdq_lowrank.hip
+hipError_t launch_lowrank_down(const void* x, int64_t ldx, const float* inv_lambda, const void* L1,
+                               int64_t M, int K, int r, float* h, hipStream_t stream);
+hipError_t launch_lowrank_up(const float* h, const void* L2, int64_t M, int N, int r,
+                             void* y, int64_t ldy, hipStream_t stream);
+
+}  // namespace svdq

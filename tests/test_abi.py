@@ -1,0 +1,79 @@
+"""Host-side checks of the C-ABI library: it loads, exports what include/svdq.h declares,
+validates arguments before touching a GPU, and its host helper matches the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+
+import paper_2605_27003_amd as svdq
+from paper_2605_27003_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "svdq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(svdq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = svdq.load_library()
+    names = declared_functions()
+    assert len(names) >= 11
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(binding.EXPORTS)
+
+
+def test_sizes_and_version():
+    assert svdq.version() >= 1
+    assert svdq.packed_l1_bytes(5120) == 5120 * 128
+    assert svdq.packed_l1_bytes(100) == 0
+    assert svdq.packed_weight_bytes(5120, 5120) >= 5120 * 2560
+    assert svdq.packed_weight_bytes(100, 5120) == 0
+
+
+def test_argument_errors_before_any_launch():
+    lib = svdq.load_library()
+    a = ctypes.c_void_p(256)                     # never dereferenced: checks fail first
+    z = ctypes.c_void_p(0)
+    INV, SHAPE = -1, -2
+    q = lib.svdq_quantize_act
+    assert q(z, 512, a, 0.9, z, 4, 512, 0, a, a, z, z) == INV                 # NULL x
+    assert q(a, 512, a, 0.0, z, 4, 512, 0, a, a, z, z) == INV                 # rho = 0
+    assert q(a, 512, a, 1.5, z, 4, 512, 0, a, a, z, z) == INV                 # rho > 1
+    assert q(a, 512, a, float("nan"), z, 4, 512, 0, a, a, z, z) == INV
+    assert q(a, 512, a, 0.9, z, -1, 512, 0, a, a, z, z) == INV                # M < 0
+    assert q(a, 512, a, 0.9, z, 4, 512, 16, a, a, z, z) == INV                # r without packed L1
+    assert q(a, 512, a, 0.9, a, 4, 512, 16, a, a, z, z) == INV                # packed L1 without h
+    assert q(a, 512, a, 0.9, z, 4, 500, 0, a, a, z, z) == SHAPE               # K % 64
+    assert q(a, 256, a, 0.9, z, 4, 512, 0, a, a, z, z) == SHAPE               # ldx < K
+    assert q(a, 512, a, 0.9, a, 4, 512, 8, a, a, a, z) == SHAPE               # rank 8
+    assert q(ctypes.c_void_p(260), 512, a, 0.9, z, 4, 512, 0, a, a, z, z) == SHAPE   # misaligned
+    assert q(a, 512, a, 0.9, z, 0, 512, 0, a, a, z, z) == 0                   # M == 0 no-op
+    g = lib.svdq_linear_w4a4
+    assert g(z, a, a, z, z, z, 4, 512, 512, 0, a, 512, 0, z) == INV
+    assert g(a, a, a, a, z, z, 4, 512, 512, 16, a, 512, 0, z) == INV          # h without L2
+    assert g(a, a, a, z, z, z, 4, 512, 512, 0, a, 512, 7, z) == INV           # bad out dtype
+    assert g(a, a, a, z, z, z, 4, 500, 512, 0, a, 512, 0, z) == SHAPE         # N % 128
+    assert g(a, a, a, z, z, z, 4, 512, 512, 0, a, 256, 0, z) == SHAPE         # ldy < N
+    assert g(a, a, a, z, z, z, 0, 512, 512, 0, a, 512, 0, z) == 0
+    assert lib.svdq_pack_weight(z, a, 512, 512, a, z) == INV
+    assert lib.svdq_pack_weight(a, a, 512, 100, a, z) == SHAPE
+    assert lib.svdq_pack_lowrank_down(a, z, 512, 16, a, z) == INV
+    assert lib.svdq_pack_lowrank_down(a, a, 512, 24, a, z) == SHAPE
+    assert lib.svdq_lowrank(2, a, 512, a, a, 4, 512, 512, 16, a, a, 512, z) == INV
+    assert lib.svdq_debug_group_acc(a, a, 4, 512, 512, 2, 8, a, z) == INV     # rows beyond M
+    assert lib.svdq_status_string(-2) == b"unsupported shape"
+
+
+def test_alpha_lookup_matches_oracle(oracle):
+    table = [0.9, 0.8, 0.8, 0.9, 0.7, 0.8, 0.6, 1.0]
+    for nbins in (1, 4, 8):
+        for step0, n in ((0, 20), (20, 20), (0, 40), (5, 3)):
+            for step in range(step0 - 2, step0 + n + 2):
+                a = svdq.alpha_lookup(table[:nbins], step, step0, n)
+                b = oracle.alpha_lookup(table[:nbins], step, step0, n)
+                assert (np.isnan(a) and np.isnan(b)) or a == b

@@ -1,0 +1,199 @@
+"""GPU-vs-oracle parity through the C ABI at sizes the oracle finishes in seconds.
+
+Bar: int4 codes, binary32 scales and int32 group accumulators bit-exact; the
+bf16 output within relative Frobenius 2e-3 and max-abs 1e-2*rms(y) (see
+helpers.check_y for how the max-abs bound is applied to a bf16 output).
+"""
+import numpy as np
+import pytest
+import torch
+
+from workloads import synth
+from tests.helpers import DeviceLayer, check_y, dev, host_bits, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def svdq():
+    import paper_2605_27003_amd as m
+    m.load_library(build_if_missing=False)
+    assert torch.cuda.is_available()
+    return m
+
+
+def small_layer(seed, M, K, N, r, outliers=3):
+    x, cm = synth.make_x(seed, M, K, outlier_count=outliers, outlier_scale=30.0)
+    L = synth.make_layer(seed, K, N, r, cm)
+    return x, L
+
+
+def run_quant(svdq, x_bits, DL, rho, ldx=None):
+    xt = dev(x_bits)
+    if ldx is not None:                                   # row-strided input
+        buf = torch.zeros((x_bits.shape[0], ldx), dtype=torch.bfloat16, device="cuda")
+        buf[:, : x_bits.shape[1]] = xt
+        xt = buf[:, : x_bits.shape[1]]
+    qx, sx, h = svdq.quantize_act(xt, DL.inv_lambda, rho, DL.l1p, DL.L.r)
+    torch.cuda.synchronize()
+    return qx, sx, h
+
+
+def check_quant(oracle, x_bits, L, rho, qx, sx, h, where):
+    oq, os_ = oracle.quantize_act(x_bits, L.inv_lambda, rho)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), os_.view(np.uint32)), where + " scales"
+    assert np.array_equal(qx.cpu().numpy(), oq), where + " codes"
+    oh = None
+    if L.r:
+        oh = oracle.lowrank_down(x_bits, L.inv_lambda, L.L1)
+        hg = h.cpu().numpy().astype(np.float64)
+        # hi+lo bf16 split of inv_lambda*L1 keeps 16 significant bits (2^-17 per term),
+        # the matrix core sums K terms in binary32
+        assert rel_fro(hg, oh) <= 3e-5, (where, rel_fro(hg, oh))
+        assert np.abs(hg - oh).max() <= 2e-4 * np.sqrt(np.mean(oh ** 2)), where
+    return oq, os_, oh
+
+
+@pytest.mark.parametrize("rho", [1.0, 0.9, 0.6])
+def test_c1_full_layer(svdq, oracle, rho):
+    w = synth.workload(0)
+    L, x = w.layers["e0/lin"], w.x["x"]
+    DL = DeviceLayer(L)
+    qx, sx, h = run_quant(svdq, x, DL, rho)
+    oq, os_, oh = check_quant(oracle, x, L, rho, qx, sx, h, f"c1 rho={rho}")
+    acc = svdq.debug_group_acc(qx, DL.wp, L.N, 0, x.shape[0]).cpu().numpy()
+    assert np.array_equal(acc, oracle.group_acc(oq, L.qw)), "group accumulators"
+    y16 = svdq.linear_w4a4(qx, sx, DL.wp, L.N, h, DL.L2, DL.bias)
+    y32 = svdq.linear_w4a4(qx, sx, DL.wp, L.N, h, DL.L2, DL.bias, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    orc = oracle.linear(oq, os_, L.qw, L.sw, oh, L.L2, L.bias)
+    check_y(host_bits(y16), y32.cpu().numpy(), orc, f"c1 rho={rho}")
+
+
+@pytest.mark.parametrize("M,K,N,r", [(333, 1024, 256, 32), (130, 192, 128, 16), (1, 64, 128, 16),
+                                     (127, 5120, 384, 32), (200, 2048, 128, 0)])
+def test_ragged_shapes(svdq, oracle, M, K, N, r):
+    x, L = small_layer(7 + M, M, K, N, r)
+    DL = DeviceLayer(L)
+    rho = 0.8
+    qx, sx, h = run_quant(svdq, x, DL, rho)
+    oq, os_, oh = check_quant(oracle, x, L, rho, qx, sx, h, f"M{M} K{K}")
+    m0 = max(0, M - 70)
+    acc = svdq.debug_group_acc(qx, DL.wp, N, m0, M - m0).cpu().numpy()
+    assert np.array_equal(acc, oracle.group_acc(oq[m0:], L.qw))
+    y16 = svdq.linear_w4a4(qx, sx, DL.wp, N, h, DL.L2, DL.bias)
+    y32 = svdq.linear_w4a4(qx, sx, DL.wp, N, h, DL.L2, DL.bias, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    orc = oracle.linear(oq, os_, L.qw, L.sw, oh, L.L2 if r else None, L.bias)
+    check_y(host_bits(y16), y32.cpu().numpy(), orc, f"M{M} K{K} N{N} r{r}")
+
+
+def test_strided_input_and_output(svdq, oracle):
+    M, K, N, r = 77, 512, 256, 16
+    x, L = small_layer(3, M, K, N, r)
+    DL = DeviceLayer(L)
+    qx, sx, h = run_quant(svdq, x, DL, 0.7, ldx=K + 64)
+    oq, os_, oh = check_quant(oracle, x, L, 0.7, qx, sx, h, "strided")
+    ybuf = torch.full((M, N + 24), 7.0, dtype=torch.bfloat16, device="cuda")
+    y = svdq.linear_w4a4(qx, sx, DL.wp, N, h, DL.L2, None, out=ybuf[:, :N])
+    y32 = svdq.linear_w4a4(qx, sx, DL.wp, N, h, DL.L2, None, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    orc = oracle.linear(oq, os_, L.qw, L.sw, oh, L.L2, None)
+    check_y(host_bits(y), y32.cpu().numpy(), orc, "strided")
+    assert torch.all(ybuf[:, N:] == 7.0)                       # padding untouched
+
+
+def test_degenerate_groups_and_ties(svdq, oracle):
+    """All-zero rows and groups, a denormal group, the hand-worked tie vectors, codes at both range ends."""
+    K = 256
+    x = np.zeros((6, K), np.float32)
+    x[1, 64:128] = np.linspace(-3, 3, 64)
+    x[2, :64] = 1e-39
+    ties = [14.0, 0.5, 1.5, 2.5, 3.5, -0.5, -1.5, -2.5, 6.5, 7.5, 8.0, -7.5, -8.5, -9.0, -14.0, 0.25, 0.75, -0.75]
+    x[3, : len(ties)] = ties
+    x[4] = np.random.default_rng(0).standard_normal(K) * 100
+    x[5, ::64] = 3e38
+    xb = synth.to_bf16_bits(x)
+    L = synth.make_layer(11, K, 128, 16, np.ones(K, np.float32))
+    L.inv_lambda[:] = 1.0
+    DL = DeviceLayer(L)
+    for rho in (0.5, 1.0):
+        qx, sx, h = run_quant(svdq, xb, DL, rho)
+        oq, os_ = oracle.quantize_act(xb, L.inv_lambda, rho)
+        assert np.array_equal(sx.cpu().numpy().view(np.uint32), os_.view(np.uint32))
+        assert np.array_equal(qx.cpu().numpy(), oq)
+    c = synth.unpack_int4(oracle.quantize_act(xb, L.inv_lambda, 0.5)[0])
+    assert c.min() == -8 and c.max() == 7 and not c[0].any()
+
+
+def test_extreme_codes_accumulators(svdq, oracle):
+    """Every code -8 on both sides: each group accumulator is 4096, the largest the path can see."""
+    M, K, N = 128, 256, 128
+    qx = np.full((M, K // 2), 0x88, np.uint8)
+    qw = np.full((N, K // 2), 0x88, np.uint8)
+    qw[1::2] = 0x77                                             # rows of +7: accumulators -3584
+    sw = np.ones((K // 64, N), np.float32)
+    import paper_2605_27003_amd as m
+    wp = m.pack_weight(dev(qw), dev(sw))
+    acc = m.debug_group_acc(dev(qx), wp, N, 0, M).cpu().numpy()
+    assert np.array_equal(acc, oracle.group_acc(qx, qw))
+    assert acc.max() == 4096 and acc.min() == -3584
+    sx = np.ones((M, K // 64), np.float32)
+    y = m.linear_w4a4(dev(qx), dev(sx), wp, N, out_dtype=torch.float32).cpu().numpy()
+    want = oracle.linear(qx, sx, qw, sw)["y64"]
+    assert np.array_equal(y.astype(np.float64), want)
+
+
+def test_unfused_lowrank_matches(svdq, oracle):
+    M, K, N, r = 150, 640, 256, 32
+    x, L = small_layer(5, M, K, N, r)
+    DL = DeviceLayer(L)
+    h = svdq.lowrank(0, x_bf16=dev(x), inv_lambda=DL.inv_lambda, L_bf16=DL.L1)
+    oh = oracle.lowrank_down(x, L.inv_lambda, L.L1)
+    assert rel_fro(h.cpu().numpy(), oh) <= 1e-5
+    y0 = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    svdq.lowrank(1, L_bf16=DL.L2, h=h, y_bf16=y0)
+    want = oh @ synth.bf16_bits_to_f32(L.L2).astype(np.float64)
+    got = synth.bf16_bits_to_f32(host_bits(y0)).astype(np.float64)
+    assert rel_fro(got, want) <= 3e-3                            # one bf16 rounding of the sum
+    # fused and un-fused down-projection agree
+    _, _, hf = run_quant(svdq, x, DL, 0.9)
+    assert rel_fro(hf.cpu().numpy(), h.cpu().numpy()) <= 3e-5
+
+
+def test_h_independent_of_rho_and_codes_of_l1(svdq, oracle):
+    M, K, N, r = 96, 512, 128, 32
+    x, L = small_layer(9, M, K, N, r)
+    DL = DeviceLayer(L)
+    q1, s1, h1 = run_quant(svdq, x, DL, 0.6)
+    q2, s2, h2 = run_quant(svdq, x, DL, 1.0)
+    assert torch.equal(h1, h2) and not torch.equal(q1, q2)
+    qn, sn, _ = svdq.quantize_act(dev(x), DL.inv_lambda, 0.6)
+    assert torch.equal(qn, q1) and torch.equal(sn, s1)
+
+
+def test_determinism_and_guard_bands(svdq):
+    """Two runs are bitwise equal and nothing is written outside the output buffers."""
+    M, K, N, r = 200, 1024, 256, 32
+    x, L = small_layer(13, M, K, N, r)
+    DL = DeviceLayer(L)
+    xt = dev(x)
+    pad = 64
+    qbuf = torch.full((M * K // 2 + 2 * pad,), 0xAB, dtype=torch.uint8, device="cuda")
+    sbuf = torch.full((M * K // 64 + 2 * pad,), -7.0, dtype=torch.float32, device="cuda")
+    hbuf = torch.full((M * r + 2 * pad,), -7.0, dtype=torch.float32, device="cuda")
+    ybuf = torch.full((M * N + 2 * pad,), -7.0, dtype=torch.bfloat16, device="cuda")
+    qx = qbuf[pad:-pad].view(M, K // 2)
+    sx = sbuf[pad:-pad].view(M, K // 64)
+    h = hbuf[pad:-pad].view(M, r)
+    y = ybuf[pad:-pad].view(M, N)
+    svdq.quantize_act(xt, DL.inv_lambda, 0.8, DL.l1p, r, out=(qx, sx, h))
+    svdq.linear_w4a4(qx, sx, DL.wp, N, h, DL.L2, DL.bias, out=y)
+    first = [t.clone() for t in (qx, sx, h, y)]
+    svdq.quantize_act(xt, DL.inv_lambda, 0.8, DL.l1p, r, out=(qx, sx, h))
+    svdq.linear_w4a4(qx, sx, DL.wp, N, h, DL.L2, DL.bias, out=y)
+    torch.cuda.synchronize()
+    for a, b in zip(first, (qx, sx, h, y)):
+        assert torch.equal(a, b)
+    for buf, val in ((qbuf, 0xAB), (sbuf, -7.0), (hbuf, -7.0), (ybuf, -7.0)):
+        assert torch.all(buf[:pad] == val) and torch.all(buf[-pad:] == val)
