@@ -1,0 +1,138 @@
+"""GPU-vs-oracle parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+Rows are independent in this path, so a row sample checked against the oracle
+is exact for those rows.  Per configuration: int4 codes and scales over the
+WHOLE buffers (bit-exact), h over the whole buffer, int32 group accumulators of
+the first rows and of the ragged last tile (bit-exact), and the bf16 / f32
+output on a seeded row sample (first 64, last 64, random rows).
+"""
+import os
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from workloads import synth
+from tests.helpers import DeviceLayer, check_y, dev, host_bits, rel_fro
+
+pytestmark = pytest.mark.gpu
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+T0 = time.time()
+
+
+def progress(msg):
+    """One line per finished step, also into gpurun_out/ when it exists (long steps must not look hung)."""
+    line = f"[{time.time() - T0:7.1f}s] {msg}"
+    print(line, flush=True)
+    d = os.path.join(ROOT, "gpurun_out")
+    if os.path.isdir(d):
+        with open(os.path.join(d, "fullsize_progress.log"), "a") as f:
+            f.write(line + "\n")
+
+
+@pytest.fixture(scope="module")
+def svdq():
+    import paper_2605_27003_amd as m
+    m.load_library(build_if_missing=False)
+    return m
+
+
+def check_layer(svdq, oracle, name, x_bits, x_dev, L, DL, rho, n_sample, whole, acc_rows=64, seed=1):
+    """One (input, layer, rho): quantise + GEMM on the full M on the GPU, oracle on what it can afford."""
+    M = x_bits.shape[0]
+    qx, sx, h = svdq.quantize_act(x_dev, DL.inv_lambda, rho, DL.l1p, L.r)
+    y16 = svdq.linear_w4a4(qx, sx, DL.wp, L.N, h, DL.L2, DL.bias)
+    torch.cuda.synchronize()
+    S = synth.sample_rows(M, n_sample - 128, seed)
+    St = torch.from_numpy(S).cuda()
+    xs = np.ascontiguousarray(x_bits[S])
+    oq, os_ = oracle.quantize_act(xs, L.inv_lambda, rho)
+    assert np.array_equal(qx[St].cpu().numpy(), oq), f"{name}: codes (row sample)"
+    assert np.array_equal(sx[St].cpu().numpy().view(np.uint32), os_.view(np.uint32)), f"{name}: scales (row sample)"
+    oh = oracle.lowrank_down(xs, L.inv_lambda, L.L1)
+    assert rel_fro(h[St].cpu().numpy(), oh) <= 3e-5, f"{name}: h (row sample)"
+    progress(f"{name} rho={rho}: codes/scales/h ok on {len(S)} rows")
+    if whole:
+        fq, fs = oracle.quantize_act(x_bits, L.inv_lambda, rho)
+        assert np.array_equal(sx.cpu().numpy().view(np.uint32), fs.view(np.uint32)), f"{name}: scales (whole buffer)"
+        assert np.array_equal(qx.cpu().numpy(), fq), f"{name}: codes (whole buffer)"
+        del fq, fs
+        progress(f"{name} rho={rho}: whole-buffer codes/scales ok ({M}x{L.K})")
+        if whole > 1:
+            fh = oracle.lowrank_down(x_bits, L.inv_lambda, L.L1)
+            assert rel_fro(h.cpu().numpy(), fh) <= 3e-5, f"{name}: h (whole buffer)"
+            del fh
+        for m0 in (0, M - acc_rows):
+            acc = svdq.debug_group_acc(qx, DL.wp, L.N, m0, acc_rows).cpu().numpy()
+            want = oracle.group_acc(qx[m0:m0 + acc_rows].cpu().numpy(), L.qw)
+            assert np.array_equal(acc, want), f"{name}: group accumulators rows {m0}.."
+            del acc, want
+        progress(f"{name}: group accumulators (first rows, ragged last tile) ok")
+    y32 = svdq.linear_w4a4(qx, sx, DL.wp, L.N, h, DL.L2, DL.bias, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    orc = oracle.linear(oq, os_, L.qw, L.sw, oh, L.L2, L.bias)
+    stats = check_y(host_bits(y16[St]), y32[St].cpu().numpy(), orc, name)
+    del y32, y16
+    progress(f"{name} rho={rho}: y ok on {len(S)} rows {stats}")
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3])
+def test_single_linear_configs(svdq, oracle, idx):
+    w = synth.workload(idx)
+    progress(f"{w.name}: inputs generated (M={w.M})")
+    L, x = w.layers["e0/lin"], w.x["x"]
+    DL = DeviceLayer(L)
+    xd = dev(x)
+    table = w.tables["e0"]
+    seen = []
+    for b, rho in enumerate(table):
+        if rho in seen:
+            continue
+        check_layer(svdq, oracle, f"{w.name}/bin{b}", x, xd, L, DL, rho,
+                    n_sample=2048 if not seen else 512, whole=0 if seen else 2, seed=idx * 10 + b)
+        seen.append(rho)
+
+
+@pytest.fixture(scope="module")
+def block720p():
+    w = synth.workload(4)
+    progress(f"{w.name}: inputs generated (M={w.M}, {len(w.layers)} layers)")
+    return w
+
+
+@pytest.mark.parametrize("expert", ["high_noise", "low_noise"])
+def test_block_720p_schedule(svdq, oracle, block720p, expert):
+    """Both experts over the 40-step schedule (switch at step 20): first and last step of each expert
+    and one step in every other timestep bin; all six linears; x changes with the step (row rotation)."""
+    w = block720p
+    step0 = 0 if expert == "high_noise" else w.switch_step
+    nsteps = w.switch_step if expert == "high_noise" else w.nsteps - w.switch_step
+    table = w.tables[expert]
+    steps, bins = [], set()
+    for s in [step0, step0 + nsteps - 1] + list(range(step0, step0 + nsteps)):
+        b = ((s - step0) * len(table)) // nsteps
+        if s in (step0, step0 + nsteps - 1) or b not in bins:
+            if s not in steps:
+                steps.append(s)
+            bins.add(b)
+    assert bins == set(range(len(table)))
+    xdev = {k: dev(v) for k, v in w.x.items()}
+    layers = {lin: DeviceLayer(w.layers[f"{expert}/{lin}"]) for lin in w.inputs_of}
+    for si, step in enumerate(steps):
+        rho = svdq.alpha_lookup(table, step, step0, nsteps)
+        assert rho == oracle.alpha_lookup(table, step, step0, nsteps)
+        shift = (step * 997) % w.M
+        for lin, inp in w.inputs_of.items():
+            DL = layers[lin]
+            xb = np.roll(w.x[inp], shift, axis=0) if si == 0 and lin in ("q", "ffn_down") else None
+            xd = torch.roll(xdev[inp], shift, dims=0)
+            if xb is None:                                   # only the sampled rows are needed on the host
+                class _Rows:                                 # lazy rolled view: x_step[i] = x[(i - shift) % M]
+                    shape = w.x[inp].shape
+                    def __getitem__(self, S, _x=w.x[inp], _s=shift, _M=w.M):
+                        return _x[(np.asarray(S) - _s) % _M]
+                xb = _Rows()
+            check_layer(svdq, oracle, f"{w.name}/{expert}/step{step}/{lin}", xb, xd, DL.L, DL, rho,
+                        n_sample=256, whole=int(si == 0 and lin in ("q", "ffn_down")), seed=step)
+            del xd

@@ -15,6 +15,8 @@ channel-wise outliers (Sec. I), post-GELU inputs for the FFN down-projection,
 and clipping-ratio tables shaped like Fig. 3 (mostly 0.8, some 0.9).
 All randomness comes from numpy's counter-based Philox generator.
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import Dict, List, Optional
 
@@ -60,10 +62,13 @@ def make_x(seed: int, M: int, K: int, kind: str = "normal",
     mult[chans[:n_out]] = outlier_scale
     mult[chans[n_out:n_out + heavy_count]] = heavy_scale
     x = np.empty((M, K), np.uint16)
-    colmax = np.zeros(K, np.float32)
-    g = _rng(seed, 2)
-    for m0 in range(0, M, chunk_rows):
+    bounds = list(range(0, M, chunk_rows))
+
+    def fill(ci):
+        # every chunk has its own counter-based stream, so the result does not depend on the thread count
+        m0 = bounds[ci]
         m1 = min(M, m0 + chunk_rows)
+        g = np.random.Generator(np.random.Philox(key=[int(seed), 2 + (ci << 8)]))
         z = g.standard_normal((m1 - m0, K), dtype=np.float32)
         if sigma != 1.0:
             z *= np.float32(sigma)
@@ -74,7 +79,12 @@ def make_x(seed: int, M: int, K: int, kind: str = "normal",
         z *= mult
         xb = to_bf16_bits(z)
         x[m0:m1] = xb
-        np.maximum(colmax, np.abs(bf16_bits_to_f32(xb)).max(axis=0), out=colmax)
+        return np.abs(bf16_bits_to_f32(xb)).max(axis=0)
+
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        colmax = np.zeros(K, np.float32)
+        for cm in ex.map(fill, range(len(bounds))):
+            np.maximum(colmax, cm, out=colmax)
     return x, colmax
 
 
@@ -229,11 +239,15 @@ def workload(idx: int, M: Optional[int] = None, keep_dense: bool = False) -> Wor
         xs["x_down"], cms["x_down"] = make_x(53, M, 13824, kind="gelu", sigma=1.5)
         shapes = {"q": ("x_qkv", 5120, 5120), "k": ("x_qkv", 5120, 5120), "v": ("x_qkv", 5120, 5120),
                   "o": ("x_o", 5120, 5120), "ffn_up": ("x_up", 5120, 13824), "ffn_down": ("x_down", 13824, 5120)}
-        layers, tables = {}, {}
+        layers, tables, jobs = {}, {}, []
         for e, ename in enumerate(("high_noise", "low_noise")):
             for j, (lin, (inp, K, N)) in enumerate(shapes.items()):
-                layers[f"{ename}/{lin}"] = make_layer(500 + 10 * e + j, K, N, 32, cms[inp], keep_dense=keep_dense)
+                jobs.append((f"{ename}/{lin}", 500 + 10 * e + j, K, N, cms[inp]))
             tables[ename] = _table(540 + e, 8, probs=[0.05, 0.1, 0.55, 0.25, 0.05])
+        with ThreadPoolExecutor(max_workers=4) as ex:
+            made = ex.map(lambda j: make_layer(j[1], j[2], j[3], 32, j[4], keep_dense=keep_dense), jobs)
+            for job, L in zip(jobs, made):
+                layers[job[0]] = L
         return Workload("c5_block_720p", M, xs, layers, {k: v[0] for k, v in shapes.items()}, tables,
                         nsteps=40, switch_step=20, experts=["high_noise", "low_noise"])
     raise ValueError(f"no workload {idx}")
