@@ -47,7 +47,7 @@ typedef enum {
     SVDQ_ERR_HIP = -4                 /* a HIP runtime call or launch failed */
 } svdq_status;
 
-enum { SVDQ_GROUP = 64, SVDQ_N_TILE = 128, SVDQ_MAX_RANK = 32 };
+enum { SVDQ_GROUP = 64, SVDQ_N_TILE = 128, SVDQ_MAX_RANK = 32, SVDQ_MAX_K = 16384 };
 enum { SVDQ_OUT_BF16 = 0, SVDQ_OUT_F32 = 1 };
 
 const char* svdq_status_string(int status);
@@ -83,7 +83,8 @@ int svdq_pack_lowrank_down(const void* L1_bf16, const float* inv_lambda, int K, 
  * per-64-group absmax, derives the clipped scale (eq. 8-9), rounds and packs
  * int4 codes (eq. 3) and computes the low-rank down-projection h = x^ L1 on
  * the un-quantised x^ (eq. 7).
- *   x_bf16      [M, ldx] bf16, first K columns used; ldx >= K, ldx % 8 == 0
+ *   x_bf16      [M, ldx] bf16, first K columns used; ldx >= K, ldx % 8 == 0;
+ *               K <= SVDQ_MAX_K (the smoothing vector is kept in LDS)
  *   inv_lambda  [K] binary32
  *   rho         clipping ratio in (0, 1]
  *   l1_packed   from svdq_pack_lowrank_down, or NULL to skip h (then r must be 0)

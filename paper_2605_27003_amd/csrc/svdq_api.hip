@@ -74,7 +74,7 @@ int svdq_quantize_act(const void* x_bf16, int64_t ldx, const float* inv_lambda, 
     if (!x_bf16 || !inv_lambda || !qx || !sx || M < 0) return SVDQ_ERR_INVALID_ARG;
     if (!(rho > 0.0f) || !(rho <= 1.0f)) return SVDQ_ERR_INVALID_ARG;      // also rejects NaN
     if (l1_packed ? (!h) : (r != 0)) return SVDQ_ERR_INVALID_ARG;
-    if (K <= 0 || K % SVDQ_GROUP || ldx < K || ldx % 8) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (K <= 0 || K % SVDQ_GROUP || K > SVDQ_MAX_K || ldx < K || ldx % 8) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (l1_packed && !rank_ok(r)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (!aligned16(x_bf16) || !aligned16(inv_lambda) || !aligned16(qx) || !aligned16(sx) ||
         !aligned16(l1_packed) || (l1_packed && !aligned16(h)))

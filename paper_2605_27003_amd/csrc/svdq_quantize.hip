@@ -33,20 +33,113 @@ __device__ __forceinline__ float max_pair32(float v) {
     return fmaxf(bits_f(r[0]), bits_f(r[1]));
 }
 
+// s = t / 7 with one multiply and two FMAs.  With y = RN(1/7): q0 = RN(t*y), r = t - 7*q0 (exact in
+// an FMA), q1 = RN(q0 + r*y).  Checked exhaustively on the host against IEEE division for every
+// binary32 mantissa; tiny t (results near the denormal range) take the IEEE sequence.
+__device__ __forceinline__ float div7(float t) {
+    const float y7 = 0.142857149243354797363281250f;
+    float q0 = __fmul_rn(t, y7);
+    float rem = __builtin_fmaf(-7.0f, q0, t);
+    float q1 = __builtin_fmaf(rem, y7, q0);
+    return (t >= 7.8886090522101181e-31f) ? q1 : __fdiv_rn(t, 7.0f);          // 2^-100
+}
+
+// RN(1/s) from v_rcp_f32 (1 ulp) and one FMA Newton step.  Equal to IEEE division for every mantissa
+// on gfx950 as long as 1/s is a normal number (checked exhaustively on the GPU, test_gpu_parity);
+// huge s takes the IEEE sequence.
+__device__ __forceinline__ float recip_rn(float s) {
+    float r0 = __builtin_amdgcn_rcpf(s);
+    float e = __builtin_fmaf(-s, r0, 1.0f);
+    float r1 = __builtin_fmaf(e, r0, r0);
+    return (s <= 4.2535295865117308e+37f) ? r1 : __fdiv_rn(1.0f, s);           // 2^125
+}
+
+constexpr uint32_t RNE_MAGIC_BITS = 0x4B400008u;            // 1.5*2^23 + 8: rounds to integer, biases codes to [0,15]
+// sum_i RNE_MAGIC_BITS-without-the-8 * 16^i mod 2^32: what the magic's exponent bits add up to when eight
+// results are folded with w = (w << 4) + t
+constexpr uint32_t PACK_JUNK = (uint32_t)(0x4B400000ull * 0x11111111ull);
+
+// One 32-row block of one group: quantiser chain on this lane's 32 values.
+__device__ __forceinline__ void quantize_rows(const uint4 (&xv)[4], const float* __restrict__ il_lds, float rho,
+                                              uint4& codes, float& s_out) {
+    float xs[32];
+    float a = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const float4 i0 = *reinterpret_cast<const float4*>(il_lds + 8 * s);
+        const float4 i1 = *reinterpret_cast<const float4*>(il_lds + 8 * s + 4);
+        const float ilv[8] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
+        const uint32_t wds[4] = {xv[s].x, xv[s].y, xv[s].z, xv[s].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float lo = __fmul_rn(bf16lo_f(wds[j]), ilv[2 * j]);          // eq. 5 in binary32
+            float hi = __fmul_rn(bf16hi_f(wds[j]), ilv[2 * j + 1]);
+            xs[8 * s + 2 * j] = lo;
+            xs[8 * s + 2 * j + 1] = hi;
+            a = __builtin_fmaxf(a, __builtin_fmaxf(__builtin_fabsf(lo), __builtin_fabsf(hi)));
+        }
+    }
+    a = max_pair32(a);                                                  // reference magnitude of eq. 8
+
+    // eq. 8-9: s = (rho * a) / q_max ; zero or denormal scale -> empty group
+    float s = div7(__fmul_rn(rho, a));
+    const bool live = s >= 1.17549435e-38f;
+    s = live ? s : 0.0f;
+    const float inv = live ? recip_rn(s) : 0.0f;
+    s_out = s;
+
+    // eq. 3: clip(rne(x^ * (1/s)), -8, 7).  Clamping before rounding gives the same code.  Adding
+    // 1.5*2^23 + 8 rounds to nearest-even and leaves code + 8 (0..15) in the low mantissa bits, so eight
+    // results fold into a dword with shift-adds and no carries between nibbles; the folded exponent
+    // bits are a constant, and x ^ 8 turns a biased nibble back into two's complement.
+    uint32_t packed[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        uint32_t wd = 0;
+#pragma unroll
+        for (int j = 7; j >= 0; --j) {
+            float u = __fmul_rn(xs[8 * d + j], inv);
+            u = __builtin_amdgcn_fmed3f(u, -8.0f, 7.0f);
+            uint32_t t = f_bits(__fadd_rn(u, bits_f(RNE_MAGIC_BITS)));
+            wd = (wd << 4) + t;
+        }
+        packed[d] = (wd - PACK_JUNK) ^ 0x88888888u;
+    }
+    codes = uint4{packed[0], packed[1], packed[2], packed[3]};
+}
+
+// LDS map (bytes).  Codes and scales are staged here so that global stores are whole 128-byte lines:
+//   [0, 4K)                 inv_lambda[K]
+//   2 x CODE_TILE           codes of one round (4 groups x 64 rows), rows padded to 144 B, double-buffered
+//   2 x SCALE_TILE          scales of 4 rounds (16 groups x 64 rows), rows padded to 17 floats, double-buffered
+// After the main loop the same memory holds the 4 x 64 x 33 partial sums of h.
+constexpr int CODE_ROW = 144;                                  // 128 B of codes + 16 B pad (conflict-free 16-byte accesses)
+constexpr int CODE_TILE = ROWS_PER_BLOCK * CODE_ROW;
+constexpr int SCALE_ROW = 17;
+constexpr int SCALE_TILE = ROWS_PER_BLOCK * SCALE_ROW * 4;
+constexpr int HPART_BYTES = WAVES * ROWS_PER_BLOCK * 33 * 4;
+
 template <bool LOWRANK>
 __global__ __launch_bounds__(256, 2)
 void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
                      const float* __restrict__ inv_lambda, float rho,
                      const uint4* __restrict__ l1p, int64_t M, int K, int r,
                      uint8_t* __restrict__ qx, float* __restrict__ sx, float* __restrict__ h) {
-    __shared__ float hpart[WAVES][ROWS_PER_BLOCK][33];
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+    float* il_s = reinterpret_cast<float*>(smem_raw);
+    uint8_t* code_tiles = smem_raw + (size_t)K * 4;
+    float* scale_tiles = reinterpret_cast<float*>(code_tiles + 2 * CODE_TILE);
 
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
     const int rr = lane & 31;          // row inside a 32-row block
     const int hf = lane >> 5;          // which 32-k half of the group
     const int ng = K >> 6;
     const int64_t row0 = (int64_t)blockIdx.x * ROWS_PER_BLOCK;
+
+    for (int i = tid * 4; i < K; i += 1024)
+        *reinterpret_cast<float4*>(il_s + i) = *reinterpret_cast<const float4*>(inv_lambda + i);
 
     float16v acc[2];
 #pragma unroll
@@ -54,108 +147,134 @@ void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
 
-    for (int g = wave; g < ng; g += WAVES) {
-        // smoothing factors of this lane's 32 k values
-        float il[32];
-        {
-            const float4* pil = reinterpret_cast<const float4*>(inv_lambda + g * 64 + hf * 32);
+    const uint16_t* xrow[2];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                float4 t = pil[j];
-                il[4 * j + 0] = t.x; il[4 * j + 1] = t.y; il[4 * j + 2] = t.z; il[4 * j + 3] = t.w;
-            }
-        }
-        // B operands (hi and lo piece of inv_lambda*L1) of the four k-steps
-        uint4 bfrag[4][2];
-        if (LOWRANK) {
-            const uint4* pb = l1p + (size_t)g * (4 * 2 * 64) + lane;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                bfrag[s][0] = pb[(s * 2 + 0) * 64];
-                bfrag[s][1] = pb[(s * 2 + 1) * 64];
-            }
-        }
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int64_t row = row0 + 32 * b + rr;
-            const int64_t rowc = row < M ? row : M - 1;          // clamp loads of the ragged tail
-            const uint4* px = reinterpret_cast<const uint4*>(x + rowc * ldx + g * 64 + hf * 32);
-            uint4 xv[4];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) xv[s] = px[s];
+    for (int b = 0; b < 2; ++b) {
+        const int64_t row = row0 + 32 * b + rr;
+        const int64_t rowc = row < M ? row : M - 1;                     // clamp loads of the ragged tail
+        xrow[b] = x + rowc * ldx + hf * 32;
+    }
 
-            // eq. 5 in binary32, and the group's reference magnitude
-            float xs[32];
-            float a = 0.0f;
+    // software pipeline: x of this wave's NEXT group is in flight while the current one is processed.
+    // Two register buffers alternate roles (the round body is instantiated twice), so there is no copy
+    // and the wait for a prefetched group sits right before its first use, one full round later.
+    uint4 xa[2][4], xb[2][4];
+    if (wave < ng) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const uint32_t wds[4] = {xv[s].x, xv[s].y, xv[s].z, xv[s].w};
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    float lo = __fmul_rn(bf16lo_f(wds[j]), il[8 * s + 2 * j]);
-                    float hi = __fmul_rn(bf16hi_f(wds[j]), il[8 * s + 2 * j + 1]);
-                    xs[8 * s + 2 * j] = lo;
-                    xs[8 * s + 2 * j + 1] = hi;
-                    a = fmaxf(a, fmaxf(fabsf(lo), fabsf(hi)));
+            for (int s = 0; s < 4; ++s) xa[b][s] = reinterpret_cast<const uint4*>(xrow[b] + wave * 64)[s];
+    }
+    __syncthreads();
+
+    const int rounds = (ng + WAVES - 1) / WAVES;
+    auto round_body = [&](const int rd, uint4 (&xc)[2][4], uint4 (&xn)[2][4]) {
+        const int g = rd * WAVES + wave;
+        uint8_t* ctile = code_tiles + (rd & 1) * CODE_TILE;
+        float* stile = scale_tiles + ((rd >> 2) & 1) * (SCALE_TILE / 4);
+        if (g < ng) {
+            // B operands (hi and lo piece of inv_lambda*L1) of the four k-steps: issued first, used last
+            uint4 bfrag[4][2];
+            if (LOWRANK) {
+                const uint4* pb = l1p + (size_t)g * (4 * 2 * 64) + lane;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    bfrag[s][0] = pb[(s * 2 + 0) * 64];
+                    bfrag[s][1] = pb[(s * 2 + 1) * 64];
                 }
             }
-            a = max_pair32(a);
-
-            // eq. 8-9: s = (rho * a) / q_max ; zero or denormal scale -> empty group
-            float s = __fdiv_rn(__fmul_rn(rho, a), QMAX);
-            const bool live = s >= 1.17549435e-38f;
-            s = live ? s : 0.0f;
-            const float inv = live ? __fdiv_rn(1.0f, s) : 0.0f;
-
-            // eq. 3: clip(rne(x^ * (1/s)), -8, 7).  Clamping before rounding gives the
-            // same code; adding 1.5*2^23 rounds to nearest-even and leaves the two's
-            // complement integer in the low mantissa bits.
-            uint32_t packed[4];
+            // keep the L2-resident operand loads ahead of the HBM prefetch in program order: the
+            // matrix-core step then waits for them without draining the prefetch (vmcnt counts in order)
+            __builtin_amdgcn_sched_barrier(0);
+            // unconditional (the last round re-reads its own group): a load under a branch would make
+            // the compiler assume the smaller outstanding count and wait for the prefetch early
+            const int gn = (g + WAVES < ng) ? g + WAVES : g;
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                uint32_t wd = 0;
+            for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int j = 7; j >= 0; --j) {
-                    float u = __fmul_rn(xs[8 * d + j], inv);
-                    u = __builtin_amdgcn_fmed3f(u, -8.0f, 7.0f);
-                    uint32_t t = f_bits(__fadd_rn(u, 12582912.0f));
-                    wd = (wd << 4) | (t & 0xFu);
-                }
-                packed[d] = wd;
-            }
-            if (row < M) {
-                uint4 o = {packed[0], packed[1], packed[2], packed[3]};
-                *reinterpret_cast<uint4*>(qx + row * (int64_t)(K >> 1) + g * 32 + hf * 16) = o;
-                if (hf == 0) sx[row * ng + g] = s;
-            }
+                for (int s = 0; s < 4; ++s) xn[b][s] = reinterpret_cast<const uint4*>(xrow[b] + gn * 64)[s];
+            __builtin_amdgcn_sched_barrier(0);
 
+            const float* il_lds = il_s + g * 64 + hf * 32;
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                uint4 codes;
+                float s;
+                quantize_rows(xc[b], il_lds, rho, codes, s);
+                const int rloc = 32 * b + rr;
+                *reinterpret_cast<uint4*>(ctile + rloc * CODE_ROW + wave * 32 + hf * 16) = codes;
+                if (hf == 0) stile[rloc * SCALE_ROW + (rd & 3) * 4 + wave] = s;
+            }
             if (LOWRANK) {
 #pragma unroll
-                for (int sidx = 0; sidx < 4; ++sidx) {
-                    bf16x8 av = __builtin_bit_cast(bf16x8, xv[sidx]);
-                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sidx][0]), acc[b], 0, 0, 0);
-                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sidx][1]), acc[b], 0, 0, 0);
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int sidx = 0; sidx < 4; ++sidx) {
+                        bf16x8 av = __builtin_bit_cast(bf16x8, xc[b][sidx]);
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sidx][0]), acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sidx][1]), acc[b], 0, 0, 0);
+                    }
+            }
+        }
+        __syncthreads();
+
+        // write-out of this round's codes: 8 consecutive lanes cover one 128-byte line of a row
+        {
+            const int piece = tid & 7;                               // 16-byte piece of the row's 128 bytes
+            const int gp = rd * WAVES + (piece >> 1);
+            if (gp < ng) {
+#pragma unroll
+                for (int pass = 0; pass < 2; ++pass) {
+                    const int rloc = pass * 32 + (tid >> 3);
+                    const int64_t row = row0 + rloc;
+                    if (row < M)
+                        *reinterpret_cast<uint4*>(qx + row * (int64_t)(K >> 1) + rd * 128 + piece * 16) =
+                            *reinterpret_cast<const uint4*>(ctile + rloc * CODE_ROW + piece * 16);
                 }
             }
         }
+        // every 4th round (and after the last one): the scales of up to 16 groups, 64 bytes per row
+        if ((rd & 3) == 3 || rd == rounds - 1) {
+            const int gbase = (rd & ~3) * WAVES;                     // first group held in this scale tile
+            const int rloc = tid >> 2, q = tid & 3;
+            const int64_t row = row0 + rloc;
+            if (row < M) {
+                const float* src = stile + rloc * SCALE_ROW + q * 4;
+                float* dst = sx + row * ng + gbase + q * 4;
+                if ((ng & 3) == 0) {
+                    if (gbase + q * 4 < ng) *reinterpret_cast<float4*>(dst) = float4{src[0], src[1], src[2], src[3]};
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (gbase + q * 4 + e < ng) dst[e] = src[e];
+                }
+            }
+        }
+    };
+    for (int rd = 0; rd < rounds; rd += 2) {
+        round_body(rd, xa, xb);
+        if (rd + 1 < rounds) round_body(rd + 1, xb, xa);
     }
 
     if (LOWRANK) {
         // D layout of the 32x32 MFMA: lane holds column (lane % 32); register i holds
         // row 8*(i/4) + 4*(lane/32) + (i%4).
+        __syncthreads();                                     // every wave is done with the staging tiles
+        float* hpart = reinterpret_cast<float*>(smem_raw);   // [WAVES][64][33]
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 int rloc = 32 * b + 8 * (i >> 2) + 4 * hf + (i & 3);
-                hpart[wave][rloc][rr] = acc[b][i];
+                hpart[(wave * ROWS_PER_BLOCK + rloc) * 33 + rr] = acc[b][i];
             }
         __syncthreads();
-        for (int idx = threadIdx.x; idx < ROWS_PER_BLOCK * r; idx += 256) {
+        for (int idx = tid; idx < ROWS_PER_BLOCK * r; idx += 256) {
             int rloc = idx / r, j = idx - rloc * r;
             int64_t row = row0 + rloc;
             if (row < M)
-                h[row * r + j] = (hpart[0][rloc][j] + hpart[1][rloc][j]) + (hpart[2][rloc][j] + hpart[3][rloc][j]);
+                h[row * r + j] = (hpart[(0 * ROWS_PER_BLOCK + rloc) * 33 + j] + hpart[(1 * ROWS_PER_BLOCK + rloc) * 33 + j]) +
+                                 (hpart[(2 * ROWS_PER_BLOCK + rloc) * 33 + j] + hpart[(3 * ROWS_PER_BLOCK + rloc) * 33 + j]);
         }
     }
 }
@@ -191,11 +310,13 @@ hipError_t launch_quantize(const void* x, int64_t ldx, const float* inv_lambda, 
                            const void* l1p, int64_t M, int K, int r,
                            uint8_t* qx, float* sx, float* h, hipStream_t stream) {
     const unsigned blocks = (unsigned)((M + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
+    size_t lds = (size_t)K * sizeof(float) + 2 * CODE_TILE + 2 * SCALE_TILE;
+    if (lds < (size_t)HPART_BYTES) lds = HPART_BYTES;
     if (l1p)
-        hipLaunchKernelGGL(quantize_kernel<true>, dim3(blocks), dim3(256), 0, stream,
+        hipLaunchKernelGGL(quantize_kernel<true>, dim3(blocks), dim3(256), lds, stream,
                            (const uint16_t*)x, ldx, inv_lambda, rho, (const uint4*)l1p, M, K, r, qx, sx, h);
     else
-        hipLaunchKernelGGL(quantize_kernel<false>, dim3(blocks), dim3(256), 0, stream,
+        hipLaunchKernelGGL(quantize_kernel<false>, dim3(blocks), dim3(256), lds, stream,
                            (const uint16_t*)x, ldx, inv_lambda, rho, (const uint4*)nullptr, M, K, r, qx, sx, h);
     return hipGetLastError();
 }
