@@ -25,9 +25,16 @@
  *     the host BEFORE any launch, so an error means nothing was enqueued.
  *     M == 0 is a successful no-op.  NaN/Inf inputs give unspecified outputs.
  *   - Row-major everywhere.  bf16 = upper half of an IEEE binary32.
- *   - Canonical packed int4: byte j of a row holds code 2j in its low nibble
- *     and code 2j+1 in its high nibble, 4-bit two's complement.
+ *   - Packed int4: within a row, byte j holds code 2j in its low nibble and code
+ *     2j+1 in its high nibble, 4-bit two's complement.
  *   - Group size is 64 along K; K % 64 == 0.
+ *   - Quantised ACTIVATIONS are stored group-major: codes qx[K/64][M][32 bytes]
+ *     (the 32 bytes = the 64 codes of token m in group g, packed as above) and
+ *     scales sx[K/64][M].  The quantise kernel produces a group of 32..64 tokens at
+ *     a time and the GEMM consumes a group of 128 tokens at a time, so this order
+ *     makes both sides' HBM accesses contiguous.  The token-major view is
+ *     qx_tm[m][g*32 + b] = qx[g][m][b], sx_tm[m][g] = sx[g][m].
+ *   - Weight codes handed to svdq_pack_weight are channel-major: qw[N][K/2].
  */
 #ifndef SVDQ_H
 #define SVDQ_H
@@ -88,9 +95,9 @@ int svdq_pack_lowrank_down(const void* L1_bf16, const float* inv_lambda, int K, 
  *   inv_lambda  [K] binary32
  *   rho         clipping ratio in (0, 1]
  *   l1_packed   from svdq_pack_lowrank_down, or NULL to skip h (then r must be 0)
- *   qx          out [M, K/2] canonical packed codes
- *   sx          out [M, K/64] binary32 scales; a group whose scale would not be a
- *               normal number gets scale 0 and codes 0
+ *   qx          out [K/64, M, 32] group-major packed codes (M*K/2 bytes)
+ *   sx          out [K/64, M] group-major binary32 scales; a group whose scale would
+ *               not be a normal number gets scale 0 and codes 0
  *   h           out [M, r] binary32 (ignored when l1_packed == NULL)
  * Bit-exact contract: x^ = x * inv_lambda, a = max|x^|, s = (rho*a)/7,
  * q = clip(rne(x^ * (1/s))), each a single IEEE binary32 operation.
@@ -101,7 +108,7 @@ int svdq_quantize_act(const void* x_bf16, int64_t ldx, const float* inv_lambda, 
 
 /*
  * One-time, offline: canonical residual codes + scales -> kernel-private layout.
- *   qw        [N, K/2] canonical packed int4 codes of the residual R (eq. 6)
+ *   qw        [N, K/2] channel-major packed int4 codes of the residual R (eq. 6)
  *   sw        [K/64, N] binary32 scales
  *   w_packed  out, svdq_packed_weight_bytes(N, K) bytes (codes stay 4-bit)
  * N % 128 == 0.
@@ -142,7 +149,8 @@ int svdq_lowrank(int mode, const void* x_bf16, int64_t ldx, const float* inv_lam
 /*
  * Test hook: the int32 group accumulators acc[m,n,g] = sum_{k in g} q[m,k] qw[n,k]
  * exactly as the GEMM kernel's matrix-core path forms them, for rows
- * [m0, m0+mt) of an M-row problem:  acc out [mt, N, K/64] int32.
+ * [m0, m0+mt) of an M-row problem (qx group-major as above):
+ * acc out [mt, N, K/64] int32.
  */
 int svdq_debug_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int N, int K,
                          int64_t m0, int mt, int32_t* acc, void* stream);

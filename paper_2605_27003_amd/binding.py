@@ -98,13 +98,15 @@ def pack_weight(qw, sw):
 
 
 def quantize_act(x_bf16, inv_lambda, rho, l1_packed=None, r=0, out=None):
-    """x [M,K] bf16 (row stride allowed) -> (qx [M,K/2] u8, sx [M,K/64] f32, h [M,r] f32 or None)."""
+    """x [M,K] bf16 (row stride allowed) -> (qx [K/64,M,32] u8, sx [K/64,M] f32, h [M,r] f32 or None).
+
+    qx and sx are group-major (see include/svdq.h); `to_token_major` gives the [M,K/2] / [M,K/64] view."""
     M, K = x_bf16.shape
     assert x_bf16.dtype == torch.bfloat16 and x_bf16.stride(1) == 1
     dev = x_bf16.device
     if out is None:
-        qx = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
-        sx = torch.empty((M, K // 64), dtype=torch.float32, device=dev)
+        qx = torch.empty((K // 64, M, 32), dtype=torch.uint8, device=dev)
+        sx = torch.empty((K // 64, M), dtype=torch.float32, device=dev)
         h = torch.empty((M, r), dtype=torch.float32, device=dev) if l1_packed is not None else None
     else:
         qx, sx, h = out
@@ -115,10 +117,22 @@ def quantize_act(x_bf16, inv_lambda, rho, l1_packed=None, r=0, out=None):
     return qx, sx, h
 
 
+def to_token_major(qx, sx):
+    """Group-major (qx [K/64,M,32], sx [K/64,M]) -> token-major copies (qx [M,K/2], sx [M,K/64])."""
+    ng, M, _ = qx.shape
+    return qx.permute(1, 0, 2).reshape(M, ng * 32).contiguous(), sx.t().contiguous()
+
+
+def to_group_major(qx_tm, sx_tm):
+    """Token-major (qx [M,K/2], sx [M,K/64]) -> group-major copies, the layout the GEMM consumes."""
+    M, K2 = qx_tm.shape
+    return qx_tm.reshape(M, K2 // 32, 32).permute(1, 0, 2).contiguous(), sx_tm.t().contiguous()
+
+
 def linear_w4a4(qx, sx, w_packed, N, h=None, L2_bf16=None, bias=None, out=None, out_dtype=torch.bfloat16):
-    """-> y [M,N] bf16 (or f32 when out_dtype is torch.float32: the value before the bf16 rounding)."""
-    M, K2 = qx.shape
-    K = 2 * K2
+    """qx [K/64,M,32], sx [K/64,M] (group-major) -> y [M,N] bf16 (or f32: the value before the bf16 rounding)."""
+    ng, M, _ = qx.shape
+    K = 64 * ng
     r = 0 if h is None else h.shape[1]
     if out is None:
         out = torch.empty((M, N), dtype=out_dtype, device=qx.device)
@@ -151,8 +165,8 @@ def lowrank(mode, *, x_bf16=None, inv_lambda=None, L_bf16=None, h=None, y_bf16=N
 
 def debug_group_acc(qx, w_packed, N, m0, mt):
     """int32 group accumulators of rows [m0, m0+mt) as the GEMM kernel forms them -> [mt, N, K/64]."""
-    M, K2 = qx.shape
-    K = 2 * K2
+    ng, M, _ = qx.shape
+    K = 64 * ng
     acc = torch.empty((mt, N, K // 64), dtype=torch.int32, device=qx.device)
     _check(load_library().svdq_debug_group_acc(_ptr(qx), _ptr(w_packed), M, N, K, m0, mt, _ptr(acc), _stream()),
            "svdq_debug_group_acc")
@@ -174,8 +188,8 @@ class W4A4Linear:
 
     def buffers(self, M, device):
         if self._bufs is None or self._bufs[0].shape[0] != M:
-            qx = torch.empty((M, self.K // 2), dtype=torch.uint8, device=device)
-            sx = torch.empty((M, self.K // 64), dtype=torch.float32, device=device)
+            qx = torch.empty((self.K // 64, M, 32), dtype=torch.uint8, device=device)
+            sx = torch.empty((self.K // 64, M), dtype=torch.float32, device=device)
             h = torch.empty((M, self.r), dtype=torch.float32, device=device) if self.r else None
             y = torch.empty((M, self.N), dtype=torch.bfloat16, device=device)
             self._bufs = (qx, sx, h, y)
@@ -186,7 +200,7 @@ class W4A4Linear:
         return quantize_act(x_bf16, self.inv_lambda, rho, self.l1_packed, self.r, out=(qx, sx, h))
 
     def gemm(self, qx, sx, h):
-        y = self.buffers(qx.shape[0], qx.device)[3]
+        y = self.buffers(qx.shape[1], qx.device)[3]
         return linear_w4a4(qx, sx, self.w_packed, self.N, h, self.L2, self.bias, out=y)
 
     def forward(self, x_bf16, rho):

@@ -11,6 +11,7 @@ typedef int   int16v  __attribute__((ext_vector_type(16)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));
 
 constexpr int GROUP = 64;            // quantisation group along K
 constexpr float QMAX = 7.0f;         // q_max of the int4 grid; codes are clamped to [-8, 7]

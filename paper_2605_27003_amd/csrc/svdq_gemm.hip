@@ -2,25 +2,33 @@
 // accumulator per 64-group, binary32 dequantisation, and the fused epilogue
 // y = main + h L2 + bias (eq. 7 / eq. 11).
 //
-// Block tile 128 (tokens) x 128 (output channels), 4 waves of 64 x 64, one
-// 64-group per main-loop step, two LDS stages.
+// The fp32 dequant step y += acc * sx[m,g] * sw[g,n] is what bounds this kernel:
+// per 32x32 tile and group the int8 matrix core needs 64 clocks, while two FMAs
+// per output on the (non-packed) vector ALU need 128.  So the work is moved:
 //
-// int4 -> int8 without sign extension.  A packed dword holds 8 nibbles; `v &
-// 0xF0F0F0F0` leaves the odd codes as 16*q in each byte and `(v << 4) &
-// 0xF0F0F0F0` does the same for the even codes.  Both operands are scaled by
-// 16, the K order inside a group is permuted identically for activations and
-// weights (an integer dot product does not care), so the matrix core returns
-// 256 * sum q_x q_w.  The unpack happens once per block when a tile is staged
-// into LDS, not per wave.
+//  * int4 -> int8 without sign extension.  `v & 0xF0F0F0F0` leaves the odd codes
+//    of a packed dword as 16*q per byte, `(v << 4) & 0xF0F0F0F0` the even ones.
+//    Both operands are scaled by 16 and the K order inside a group is permuted
+//    identically on both sides, so the MFMA returns 256 * sum q_x q_w.
+//  * int32 -> binary32 for free.  The first MFMA of a group starts from the bit
+//    pattern of 2.25f.  256*acc fits in the mantissa below and above it, so the
+//    int32 result read as a float IS f = 2.25 + acc * 2^-14, exactly.
+//  * the scale product S[n][m] = (sx[m,g] * 2^14) * sw[g,n] of a tile is an outer
+//    product, i.e. a matrix product with K = 1: the bf16 matrix core forms it
+//    from hi+lo bf16 pieces of both scales (4 products, 16 significant bits).
+//    The vector ALU is left with ONE FMA per output and group: y += f * S.
+//  * that FMA also adds 2.25 * S.  Every second group a bf16 MFMA subtracts
+//    2.25 * (S_g + S_{g+1}) straight into y (2.25 = 2 + 1/4, both exact factors
+//    on bf16 pieces, same four products as S), so y never drifts far from the
+//    true partial sum.
 //
-// int32 -> binary32 for free.  The first MFMA of a group starts from the bit
-// pattern of 3.0f instead of 0.  256*acc fits in the mantissa below it, so the
-// int32 result, read as a float, IS 3 + acc * 2^-14, exactly.  The dequant
-// step is then two FMAs per output and group:
-//     t = f * (sx * 2^14) + (-3 * sx * 2^14)      ( = acc * sx )
-//     y = t * sw + y
-// Orientation: the MFMA computes the transposed tile D[n][m], so a lane owns
-// one token m (its sx terms are per-lane scalars) and 16 output channels n.
+// Orientation: the MFMA computes the transposed tile D[n][m] (weights are the A
+// operand).  Everything the matrix cores consume reaches them through LDS, staged
+// one stage (two groups) ahead by the whole block, so the compute path has no
+// global-memory waits: activations are unpacked to 16*q bytes while being staged;
+// weights stay 4-bit in LDS (prepacked offline in fragment order) and are unpacked
+// in registers; the bf16 pieces of the weight scales and the correction operands
+// are prepacked offline too.  Block tile 128 x 128, 4 waves of 64 x 64.
 #include "svdq_dev.h"
 #include "svdq_kernels.h"
 
@@ -29,37 +37,52 @@ namespace svdq {
 namespace {
 
 constexpr int BM = 128, BN = 128;
-constexpr int LDS_ROW = 80;                 // 64 operand bytes + 16 pad: conflict-free 16-byte reads
-constexpr uint32_t MAGIC_BITS = 0x40400000u;   // 3.0f
-constexpr float SX_SCALE = 16384.0f;        // 2^14 = 2^22 / 256
+constexpr int GS = 2;                          // groups per LDS stage
+constexpr int LDS_ROW = 80;                    // 64 operand bytes + 16 pad: conflict-free 16-byte reads
+constexpr uint32_t MAGIC_BITS = 0x40100000u;   // 2.25f
+constexpr float SX_SCALE = 16384.0f;           // 2^14 = 2^22 / 256
 
 struct Stage {
-    uint8_t a[BM * LDS_ROW];                // activations, 16*q per byte
-    uint8_t w[BN * LDS_ROW];                // weights, 16*q per byte
-    float sr[BM];                           // sx * 2^14
-    float sw[BN];
+    uint8_t a[GS][BM * LDS_ROW];               // activations, 16*q per byte, chunk = 2*(odd codes) + 16-byte half
+    uint4 w[GS][BN / 32][64];                  // weight fragments, still 4-bit: [group][n-block][lane]
+    uint2 sxs[GS][BM];                         // {p, p}: m-side operand of the scale-product MFMA (K = 8), p = bf16 hi | lo << 16 of sx*2^14
+    uint2 sfr[GS][BN / 32][32];                // n-side operand of the scale-product MFMA: bf16 {w1, w1, w2, w2}
+    uint4 cfr[BN / 32][64];                    // n-side operand of the correction MFMA for this pair of groups
 };
 
-__device__ __forceinline__ void unpack_store(uint8_t* dst_row, int p, uint4 v) {
+__device__ __forceinline__ void unpack_store(uint8_t* dst_row, int sp, uint4 v) {
     uint4 lo, hi;
     lo.x = (v.x << 4) & 0xF0F0F0F0u; hi.x = v.x & 0xF0F0F0F0u;
     lo.y = (v.y << 4) & 0xF0F0F0F0u; hi.y = v.y & 0xF0F0F0F0u;
     lo.z = (v.z << 4) & 0xF0F0F0F0u; hi.z = v.z & 0xF0F0F0F0u;
     lo.w = (v.w << 4) & 0xF0F0F0F0u; hi.w = v.w & 0xF0F0F0F0u;
-    *reinterpret_cast<uint4*>(dst_row + (2 * p) * 16) = lo;
-    *reinterpret_cast<uint4*>(dst_row + (2 * p + 1) * 16) = hi;
+    *reinterpret_cast<uint4*>(dst_row + sp * 16) = lo;            // k-step 0: even codes
+    *reinterpret_cast<uint4*>(dst_row + (2 + sp) * 16) = hi;      // k-step 1: odd codes
 }
+
+// hi | lo << 16 bf16 pieces of v (16 significant bits)
+__device__ __forceinline__ uint32_t split_bf16(float v) {
+    const uint32_t hi = f_bf16_rne(v);
+    const uint32_t lo = f_bf16_rne(v - bits_f(hi << 16));
+    return hi | (lo << 16);
+}
+
+// sizes of the packed weight regions (bytes)
+__host__ __device__ inline size_t wfrag_bytes(int N, int K) { return (size_t)N * (K / 2); }
+__host__ __device__ inline size_t sfrag_bytes(int N, int K) { return (size_t)(N / 32) * (K / 64) * 256; }
+__host__ __device__ inline size_t cfrag_bytes(int N, int K) { return (size_t)(N / 32) * ((K / 64 + 1) / 2) * 1024; }
 
 // DUMP = false: the layer.  DUMP = true: write the int32 group accumulators of
 // rows [dm0, dm0 + dmt) instead of y.
 template <bool DUMP>
 __global__ __launch_bounds__(256, 2)
 void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
-                 const uint8_t* __restrict__ wq, const float* __restrict__ sw,
+                 const uint4* __restrict__ wfrag, const uint2* __restrict__ sfrag, const uint4* __restrict__ cfrag,
                  const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
-                 int64_t M, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
+                 int64_t M, int64_t ldm, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
                  int mtiles, int ntiles, int64_t dm0, int dmt, int32_t* __restrict__ dacc) {
     __shared__ __attribute__((aligned(16))) Stage stage[2];
+    __shared__ __attribute__((aligned(16))) uint2 zero_entry;
 
     // XCD-aware tile order: consecutive block ids go round-robin to the 8 XCDs,
     // so give each XCD its own token tiles and walk them 8 at a time across n.
@@ -74,18 +97,25 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
     const int wm = wave & 1, wn = wave >> 1;
     const int l32 = lane & 31, kh = lane >> 5;
     const int ng = K >> 6;
+    const int ngp = (ng + 1) >> 1;
+    const int nstages = ngp;
     const int64_t m0 = (int64_t)mt * BM;
     const int n0 = nt * BN;
 
-    // staging assignment: thread -> (row, 16-byte half of the group's 32 packed bytes)
+    // ---- staging assignment.  Per stage (two groups) a thread moves: 2 x 16 B of activation codes,
+    // 2 x 16 B of weight fragments, 8 B of weight-scale pieces, 16 B of correction operand, one sx.
     const int srow = tid >> 1, sp = tid & 1;
     const int64_t arow = (m0 + srow < M) ? (m0 + srow) : (M - 1);
-    const uint8_t* ga = qx + arow * (int64_t)(K >> 1) + sp * 16;
-    const uint8_t* gw = wq + ((size_t)nt * ng * BN + srow) * 32 + sp * 16;
-    // scale staging: threads 0..127 fetch sw, 128..255 fetch sx
-    const int64_t sxrow = (m0 + (tid & 127) < M) ? (m0 + (tid & 127)) : (M - 1);
-    const float* gs = DUMP ? nullptr : ((tid < 128) ? (sw + n0 + tid) : (sx + sxrow * ng));
-    const int64_t gs_step = (tid < 128) ? N : 1;
+    const uint8_t* ga = qx + arow * 32 + sp * 16;                 // group-major codes: qx[g][row][32 B]
+    const int xrow = tid & 127, xg = tid >> 7;                     // sx: threads 0..127 first group, 128..255 second
+    const int64_t sxrow = (m0 + xrow < M) ? (m0 + xrow) : (M - 1);
+    const float* gsx = DUMP ? nullptr : sx + sxrow;               // group-major scales: sx[g][row]
+    const int nbB = n0 >> 5;                                       // first 32-channel block of this tile
+    const int wnb = tid >> 6;                                      // weight fragment: (n-block = tid / 64, lane = tid % 64)
+    const uint4* gw = wfrag + ((size_t)(nbB + wnb) * ng) * 64 + lane;
+    const int snb = (tid >> 5) & 3, sj = tid >> 7;                 // scale pieces: (group = tid / 128, n-block, lane % 32)
+    const uint2* gs = DUMP ? nullptr : sfrag + ((size_t)(nbB + snb) * ng) * 32 + l32;
+    const uint4* gc = DUMP ? nullptr : cfrag + ((size_t)(nbB + wnb) * ngp) * 64 + lane;
 
     float16v y[2][2];                        // [ni][mi]
 #pragma unroll
@@ -98,97 +128,147 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
     int16v magic;
 #pragma unroll
     for (int i = 0; i < 16; ++i) magic[i] = (int)MAGIC_BITS;
+    // opaque to the compiler: otherwise it rebuilds these 16 registers from a scalar before every use
+    asm volatile("" : "+v"(magic));
+    float16v zero16;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
 
-    // prologue: group 0 -> stage 0
-    {
-        uint4 va = *reinterpret_cast<const uint4*>(ga);
-        uint4 vw = *reinterpret_cast<const uint4*>(gw);
-        float sc = DUMP ? 1.0f : gs[0];
-        unpack_store(stage[0].a + srow * LDS_ROW, sp, va);
-        unpack_store(stage[0].w + srow * LDS_ROW, sp, vw);
-        if (tid < 128) stage[0].sw[tid] = sc; else stage[0].sr[tid - 128] = sc * SX_SCALE;
+    // Plain locals (not a struct): a struct passed around by reference is not split into registers and
+    // ends up in LDS, with a wait for the loads right after they are issued.
+#define SVDQ_STAGE_LOAD(s_)                                                                              \
+    {                                                                                                    \
+        const int ga_ = ((s_) * GS < ng) ? (s_) * GS : (ng - 1);                                         \
+        const int gb_ = ((s_) * GS + 1 < ng) ? (s_) * GS + 1 : (ng - 1);   /* odd tail: re-read the last group */ \
+        va0 = *reinterpret_cast<const uint4*>(ga + (size_t)ga_ * ldm * 32);                              \
+        va1 = *reinterpret_cast<const uint4*>(ga + (size_t)gb_ * ldm * 32);                              \
+        vw0 = gw[(size_t)ga_ * 64];                                                                      \
+        vw1 = gw[(size_t)gb_ * 64];                                                                      \
+        if (!DUMP) {                                                                                     \
+            const int gsj_ = ((s_) * GS + sj < ng) ? (s_) * GS + sj : (ng - 1);                          \
+            vs = gs[(size_t)gsj_ * 32];                                                                  \
+            vc = gc[(size_t)(s_) * 64];                                                                  \
+            const int gx_ = (s_) * GS + xg;                                                              \
+            sc = gsx[(size_t)(gx_ < ng ? gx_ : ng - 1) * ldm];                                           \
+            sc_live = gx_ < ng;        /* applied at store time: using sc here would wait for the load */ \
+        }                                                                                                \
     }
+#define SVDQ_STAGE_STORE(st_)                                                                            \
+    {                                                                                                    \
+        unpack_store((st_).a[0] + srow * LDS_ROW, sp, va0);                                              \
+        unpack_store((st_).a[1] + srow * LDS_ROW, sp, va1);                                              \
+        (st_).w[0][wnb][lane] = vw0;                                                                     \
+        (st_).w[1][wnb][lane] = vw1;                                                                     \
+        if (!DUMP) {                                                                                     \
+            (st_).sfr[sj][snb][l32] = vs;                                                                \
+            (st_).cfr[wnb][lane] = vc;                                                                   \
+            const uint32_t p_ = sc_live ? split_bf16(sc * SX_SCALE) : 0u;                                             \
+            (st_).sxs[xg][xrow] = uint2{p_, p_};                                                         \
+        }                                                                                                \
+    }
+    uint4 va0, va1, vw0, vw1, vc = {0u, 0u, 0u, 0u};
+    uint2 vs = {0u, 0u};
+    float sc = 0.0f;
+    bool sc_live = false;
+
+    // prologue: stage 0
+    SVDQ_STAGE_LOAD(0);
+    SVDQ_STAGE_STORE(stage[0]);
+    if (tid == 0) zero_entry = uint2{0u, 0u};
     __syncthreads();
 
-    for (int g = 0; g < ng; ++g) {
-        const Stage& cur = stage[g & 1];
-        Stage& nxt = stage[(g + 1) & 1];
-        const bool more = (g + 1 < ng);
-        uint4 va, vw;
-        float sc = 0.0f;
-        if (more) {
-            va = *reinterpret_cast<const uint4*>(ga + (size_t)(g + 1) * 32);
-            vw = *reinterpret_cast<const uint4*>(gw + (size_t)(g + 1) * BN * 32);
-            if (!DUMP) sc = gs[(int64_t)(g + 1) * gs_step];
-        }
+    for (int s = 0; s < nstages; ++s) {
+        const Stage& cur = stage[s & 1];
+        Stage& nxt = stage[(s + 1) & 1];
+        const bool more = (s + 1 < nstages);
+        if (more) SVDQ_STAGE_LOAD(s + 1);
 
-        // per-lane token scales and per-register channel scales of this group
-        float srv[2], crv[2];
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-            srv[mi] = cur.sr[wm * 64 + mi * 32 + l32];
-            crv[mi] = -3.0f * srv[mi];
-        }
-        float swv[2][16];
+        for (int j = 0; j < GS; ++j) {
+            const int g = s * GS + j;
+            if (g >= ng) break;
+
+            // every LDS operand of this group is requested up front (and the scheduler may not sink the
+            // reads next to their uses): LDS latency is then paid once per group, not once per MFMA
+            int4v xf[2][2];
+            uint2 sxs[2], sfr[2];
+            uint4 wpk[2], cn[2];
+            uint32_t cp_[2];
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
+            for (int mi = 0; mi < 2; ++mi) {
+                const int rrow = wm * 64 + mi * 32 + l32;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float4 t = *reinterpret_cast<const float4*>(&cur.sw[wn * 64 + ni * 32 + 8 * q + 4 * kh]);
-                swv[ni][4 * q + 0] = t.x; swv[ni][4 * q + 1] = t.y; swv[ni][4 * q + 2] = t.z; swv[ni][4 * q + 3] = t.w;
+                for (int ks = 0; ks < 2; ++ks)
+                    xf[mi][ks] = *reinterpret_cast<const int4v*>(cur.a[j] + rrow * LDS_ROW + (2 * ks + kh) * 16);
+                if (!DUMP) {
+                    const uint2* pe = kh ? &zero_entry : &cur.sxs[j][rrow];
+                    sxs[mi] = *pe;
+                    if (j == 0) cp_[mi] = cur.sxs[kh][rrow].x;     // lanes 0..31: group g, lanes 32..63: group g+1
+                }
             }
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                wpk[ni] = cur.w[j][wn * 2 + ni][lane];
+                if (!DUMP) {
+                    const uint2* pe = kh ? &zero_entry : &cur.sfr[j][wn * 2 + ni][l32];
+                    sfr[ni] = *pe;
+                    if (j == 0) cn[ni] = cur.cfr[wn * 2 + ni][lane];
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
 
-        int16v acc[2][2];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            int4v wf[2], xf[2];
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-                wf[ni] = *reinterpret_cast<const int4v*>(cur.w + (wn * 64 + ni * 32 + l32) * LDS_ROW + (2 * ks + kh) * 16);
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-                xf[mi] = *reinterpret_cast<const int4v*>(cur.a + (wm * 64 + mi * 32 + l32) * LDS_ROW + (2 * ks + kh) * 16);
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi)
-                    acc[ni][mi] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ni], xf[mi], ks == 0 ? magic : acc[ni][mi], 0, 0, 0);
-        }
-
-        if (DUMP) {
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
+            if (!DUMP && j == 0) {
+                // y -= 2.25 * (S_g + S_{g+1}) for the four tiles, before the two groups add it back
 #pragma unroll
                 for (int mi = 0; mi < 2; ++mi) {
-                    int64_t m = m0 + wm * 64 + mi * 32 + l32;
-                    if (m >= dm0 && m < dm0 + dmt && m < M) {
+                    const uint4 cm = {cp_[mi], cp_[mi], cp_[mi], cp_[mi]};
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            int n = n0 + wn * 64 + ni * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
-                            dacc[((m - dm0) * N + n) * ng + g] = (acc[ni][mi][i] - (int)MAGIC_BITS) >> 8;
+                    for (int ni = 0; ni < 2; ++ni)
+                        y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cn[ni]),
+                                                                            __builtin_bit_cast(bf16x8, cm), y[ni][mi], 0, 0, 0);
+                }
+            }
+
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                // int4 -> 16*q bytes, in registers (this wave's 32 output channels)
+                int4v wlo, whi;
+                const uint32_t pk[4] = {wpk[ni].x, wpk[ni].y, wpk[ni].z, wpk[ni].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    wlo[e] = (int)((pk[e] << 4) & 0xF0F0F0F0u);
+                    whi[e] = (int)(pk[e] & 0xF0F0F0F0u);
+                }
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) {
+                    int16v acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wlo, xf[mi][0], magic, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(whi, xf[mi][1], acc, 0, 0, 0);
+                    if (DUMP) {
+                        const int64_t m = m0 + wm * 64 + mi * 32 + l32;
+                        if (m >= dm0 && m < dm0 + dmt && m < M) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) {
+                                const int n = n0 + wn * 64 + ni * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
+                                dacc[((m - dm0) * N + n) * ng + g] = (acc[i] - (int)MAGIC_BITS) >> 8;
+                            }
                         }
+                    } else {
+                        const float16v S = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, sfr[ni]),
+                                                                                    __builtin_bit_cast(short4v, sxs[mi]), zero16, 0, 0, 0);
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            y[ni][mi][i] = __builtin_fmaf(bits_f((uint32_t)acc[i]), S[i], y[ni][mi][i]);
                     }
                 }
-        } else {
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        float t = __builtin_fmaf(bits_f((uint32_t)acc[ni][mi][i]), srv[mi], crv[mi]);
-                        y[ni][mi][i] = __builtin_fmaf(t, swv[ni][i], y[ni][mi][i]);
-                    }
+            }
         }
 
-        if (more) {
-            unpack_store(nxt.a + srow * LDS_ROW, sp, va);
-            unpack_store(nxt.w + srow * LDS_ROW, sp, vw);
-            if (tid < 128) nxt.sw[tid] = sc; else nxt.sr[tid - 128] = sc * SX_SCALE;
-        }
+        if (more) SVDQ_STAGE_STORE(nxt);
         __syncthreads();
     }
 
+#undef SVDQ_STAGE_LOAD
+#undef SVDQ_STAGE_STORE
     if (DUMP) return;
 
     // ---- epilogue (c): low-rank up-projection on the bf16 matrix cores, bias, store
@@ -259,31 +339,60 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
     }
 }
 
-// canonical [N, K/2] codes -> [N/128][K/64][128][32] tiles, then the scales [K/64, N]
+// Offline packing.  Region 1: weight fragments [N/32][K/64][64 lanes][16 B]: lane (n = lane % 32, kh = lane / 32)
+// holds bytes [32 g + 16 kh, +16) of row n of the canonical codes.  Region 2: n-side operands of the
+// scale-product MFMA, same indexing: lanes kh = 0 hold bf16 {w1, w1, w2, w2, 0, 0, 0, 0} with w1 + w2 ~ sw[g][n],
+// lanes kh = 1 zeros.  Region 3: n-side operands of the correction MFMA [N/32][ceil(ng/2)][64][16 B]: lane
+// (n, kh) holds, for group 2 gp + kh, bf16 {-2 w1, -2 w1, -2 w2, -2 w2, -w1/4, -w1/4, -w2/4, -w2/4}.
 __global__ void pack_weight_kernel(const uint8_t* __restrict__ qw, const float* __restrict__ sw,
                                    int N, int K, uint8_t* __restrict__ out) {
-    const int ng = K >> 6;
-    const size_t nvec = (size_t)N * (K >> 1) / 16;
-    for (size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += (size_t)gridDim.x * blockDim.x) {
-        // destination vector index -> (nt, g, row, p)
-        int p = (int)(v & 1);
-        int row = (int)((v >> 1) & 127);
-        size_t rest = v >> 8;
-        int g = (int)(rest % ng);
-        int nt = (int)(rest / ng);
-        const uint4* src = reinterpret_cast<const uint4*>(qw + ((size_t)(nt * BN + row)) * (K >> 1) + g * 32 + p * 16);
-        reinterpret_cast<uint4*>(out)[v] = *src;
+    const int ng = K >> 6, ngp = (ng + 1) >> 1;
+    const size_t stride = (size_t)gridDim.x * blockDim.x, t0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint4* o1 = reinterpret_cast<uint4*>(out);
+    const size_t n1 = (size_t)(N >> 5) * ng * 64;
+    for (size_t v = t0; v < n1; v += stride) {
+        const int lane = (int)(v & 63);
+        const size_t fr = v >> 6;
+        const int g = (int)(fr % ng), nb = (int)(fr / ng);
+        const int n = nb * 32 + (lane & 31), kh = lane >> 5;
+        o1[v] = *reinterpret_cast<const uint4*>(qw + (size_t)n * (K >> 1) + g * 32 + kh * 16);
     }
-    float* so = reinterpret_cast<float*>(out + (size_t)N * (K >> 1));
-    const size_t ns = (size_t)ng * N;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < ns; i += (size_t)gridDim.x * blockDim.x) so[i] = sw[i];
+    uint2* o2 = reinterpret_cast<uint2*>(out + wfrag_bytes(N, K));
+    const size_t n2 = (size_t)(N >> 5) * ng * 32;
+    for (size_t v = t0; v < n2; v += stride) {
+        const int l = (int)(v & 31);
+        const size_t fr = v >> 5;
+        const int g = (int)(fr % ng), nb = (int)(fr / ng);
+        const uint32_t p = split_bf16(sw[(size_t)g * N + nb * 32 + l]);
+        const uint32_t w1 = p & 0xffffu, w2 = p >> 16;
+        o2[v] = uint2{w1 | (w1 << 16), w2 | (w2 << 16)};
+    }
+    uint4* o3 = reinterpret_cast<uint4*>(out + wfrag_bytes(N, K) + sfrag_bytes(N, K));
+    const size_t n3 = (size_t)(N >> 5) * ngp * 64;
+    for (size_t v = t0; v < n3; v += stride) {
+        const int lane = (int)(v & 63);
+        const size_t fr = v >> 6;
+        const int gp = (int)(fr % ngp), nb = (int)(fr / ngp);
+        const int n = nb * 32 + (lane & 31), g = 2 * gp + (lane >> 5);
+        uint4 e = {0u, 0u, 0u, 0u};
+        if (g < ng) {
+            const uint32_t p = split_bf16(sw[(size_t)g * N + n]);
+            const float w1 = bits_f(p << 16), w2 = bits_f(p & 0xffff0000u);
+            // exact: powers of two times bf16 values (barring underflow)
+            const uint32_t a1 = f_bf16_rne(-2.0f * w1), a2 = f_bf16_rne(-2.0f * w2);
+            const uint32_t b1 = f_bf16_rne(-0.25f * w1), b2 = f_bf16_rne(-0.25f * w2);
+            e.x = a1 | (a1 << 16);
+            e.y = a2 | (a2 << 16);
+            e.z = b1 | (b1 << 16);
+            e.w = b2 | (b2 << 16);
+        }
+        o3[v] = e;
+    }
 }
 
 }  // namespace
 
-size_t packed_weight_bytes(int N, int K) {
-    return (size_t)N * (K / 2) + (size_t)(K / 64) * N * sizeof(float);
-}
+size_t packed_weight_bytes(int N, int K) { return wfrag_bytes(N, K) + sfrag_bytes(N, K) + cfrag_bytes(N, K); }
 
 hipError_t launch_pack_weight(const uint8_t* qw, const float* sw, int N, int K, void* out, hipStream_t stream) {
     hipLaunchKernelGGL(pack_weight_kernel, dim3(1024), dim3(256), 0, stream, qw, sw, N, K, (uint8_t*)out);
@@ -300,10 +409,12 @@ hipError_t launch_linear(const uint8_t* qx, const float* sx, const void* w_packe
                          int64_t M, int N, int K, int r, void* y, int64_t ldy, int out_f32,
                          hipStream_t stream) {
     const int mtiles = (int)((M + BM - 1) / BM), ntiles = N / BN;
-    const uint8_t* wq = (const uint8_t*)w_packed;
-    const float* sw = (const float*)(wq + (size_t)N * (K / 2));
+    const uint8_t* base = (const uint8_t*)w_packed;
+    const uint4* wf = (const uint4*)base;
+    const uint2* sf = (const uint2*)(base + wfrag_bytes(N, K));
+    const uint4* cf = (const uint4*)(base + wfrag_bytes(N, K) + sfrag_bytes(N, K));
     hipLaunchKernelGGL(gemm_kernel<false>, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
-                       qx, sx, wq, sw, h, (const uint16_t*)L2, bias, M, N, K, r, y, ldy, out_f32,
+                       qx, sx, wf, sf, cf, h, (const uint16_t*)L2, bias, M, M, N, K, r, y, ldy, out_f32,
                        mtiles, ntiles, (int64_t)0, 0, (int32_t*)nullptr);
     return hipGetLastError();
 }
@@ -313,13 +424,12 @@ hipError_t launch_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, 
     // only the token tiles that intersect [m0, m0 + mt) are launched
     const int t0 = (int)(m0 / BM), t1 = (int)((m0 + mt + BM - 1) / BM);
     const int mtiles = t1 - t0, ntiles = N / BN;
-    const uint8_t* wq = (const uint8_t*)w_packed;
-    const float* sw = (const float*)(wq + (size_t)N * (K / 2));
     const int64_t off = (int64_t)t0 * BM;
     // the integer accumulators need no scales: the DUMP instantiation never reads them
     hipLaunchKernelGGL(gemm_kernel<true>, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
-                       qx + off * (K / 2), (const float*)nullptr, wq, sw, (const float*)nullptr, (const uint16_t*)nullptr,
-                       (const float*)nullptr, M - off, N, K, 0, (void*)nullptr, (int64_t)0, 0,
+                       qx + off * 32, (const float*)nullptr, (const uint4*)w_packed, (const uint2*)nullptr,
+                       (const uint4*)nullptr, (const float*)nullptr, (const uint16_t*)nullptr,
+                       (const float*)nullptr, M - off, M, N, K, 0, (void*)nullptr, (int64_t)0, 0,
                        mtiles, ntiles, m0 - off, mt, acc);
     return hipGetLastError();
 }

@@ -11,6 +11,9 @@
 //     k per lane and k-step), so x goes to the matrix cores without a shuffle;
 //   - a layout in which the absmax of a group needs one cross-lane exchange
 //     (lanes l and l^32) and a lane packs 16 contiguous bytes of codes.
+// Outputs are group-major (qx[g][row][32 B], sx[g][row]): what a wave produces for
+// one group and 32 rows is 1 KB of codes and 128 B of scales, contiguous, and it is
+// also the order in which the GEMM stages them.
 // The smoothing factor is folded into the packed L1 operand offline, so the
 // matrix cores consume the exact bf16 x; the bit-exact quantiser chain runs in
 // binary32 on the vector ALU.
@@ -108,15 +111,6 @@ __device__ __forceinline__ void quantize_rows(const uint4 (&xv)[4], const float*
     codes = uint4{packed[0], packed[1], packed[2], packed[3]};
 }
 
-// LDS map (bytes).  Codes and scales are staged here so that global stores are whole 128-byte lines:
-//   [0, 4K)                 inv_lambda[K]
-//   2 x CODE_TILE           codes of one round (4 groups x 64 rows), rows padded to 144 B, double-buffered
-//   2 x SCALE_TILE          scales of 4 rounds (16 groups x 64 rows), rows padded to 17 floats, double-buffered
-// After the main loop the same memory holds the 4 x 64 x 33 partial sums of h.
-constexpr int CODE_ROW = 144;                                  // 128 B of codes + 16 B pad (conflict-free 16-byte accesses)
-constexpr int CODE_TILE = ROWS_PER_BLOCK * CODE_ROW;
-constexpr int SCALE_ROW = 17;
-constexpr int SCALE_TILE = ROWS_PER_BLOCK * SCALE_ROW * 4;
 constexpr int HPART_BYTES = WAVES * ROWS_PER_BLOCK * 33 * 4;
 
 template <bool LOWRANK>
@@ -125,10 +119,9 @@ void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
                      const float* __restrict__ inv_lambda, float rho,
                      const uint4* __restrict__ l1p, int64_t M, int K, int r,
                      uint8_t* __restrict__ qx, float* __restrict__ sx, float* __restrict__ h) {
+    // LDS: inv_lambda[K] during the main loop, then the 4 x 64 x 33 partial sums of h
     extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
     float* il_s = reinterpret_cast<float*>(smem_raw);
-    uint8_t* code_tiles = smem_raw + (size_t)K * 4;
-    float* scale_tiles = reinterpret_cast<float*>(code_tiles + 2 * CODE_TILE);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -148,10 +141,11 @@ void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
         for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
 
     const uint16_t* xrow[2];
+    int64_t rows[2];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-        const int64_t row = row0 + 32 * b + rr;
-        const int64_t rowc = row < M ? row : M - 1;                     // clamp loads of the ragged tail
+        rows[b] = row0 + 32 * b + rr;
+        const int64_t rowc = rows[b] < M ? rows[b] : M - 1;             // clamp loads of the ragged tail
         xrow[b] = x + rowc * ldx + hf * 32;
     }
 
@@ -170,8 +164,6 @@ void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
     const int rounds = (ng + WAVES - 1) / WAVES;
     auto round_body = [&](const int rd, uint4 (&xc)[2][4], uint4 (&xn)[2][4]) {
         const int g = rd * WAVES + wave;
-        uint8_t* ctile = code_tiles + (rd & 1) * CODE_TILE;
-        float* stile = scale_tiles + ((rd >> 2) & 1) * (SCALE_TILE / 4);
         if (g < ng) {
             // B operands (hi and lo piece of inv_lambda*L1) of the four k-steps: issued first, used last
             uint4 bfrag[4][2];
@@ -201,9 +193,11 @@ void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
                 uint4 codes;
                 float s;
                 quantize_rows(xc[b], il_lds, rho, codes, s);
-                const int rloc = 32 * b + rr;
-                *reinterpret_cast<uint4*>(ctile + rloc * CODE_ROW + wave * 32 + hf * 16) = codes;
-                if (hf == 0) stile[rloc * SCALE_ROW + (rd & 3) * 4 + wave] = s;
+                // group-major outputs: the 32 rows of this block are 1 KB of codes and 128 B of scales, contiguous
+                if (rows[b] < M) {
+                    *reinterpret_cast<uint4*>(qx + ((size_t)g * M + rows[b]) * 32 + hf * 16) = codes;
+                    if (hf == 0) sx[(size_t)g * M + rows[b]] = s;
+                }
             }
             if (LOWRANK) {
 #pragma unroll
@@ -216,40 +210,6 @@ void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
                     }
             }
         }
-        __syncthreads();
-
-        // write-out of this round's codes: 8 consecutive lanes cover one 128-byte line of a row
-        {
-            const int piece = tid & 7;                               // 16-byte piece of the row's 128 bytes
-            const int gp = rd * WAVES + (piece >> 1);
-            if (gp < ng) {
-#pragma unroll
-                for (int pass = 0; pass < 2; ++pass) {
-                    const int rloc = pass * 32 + (tid >> 3);
-                    const int64_t row = row0 + rloc;
-                    if (row < M)
-                        *reinterpret_cast<uint4*>(qx + row * (int64_t)(K >> 1) + rd * 128 + piece * 16) =
-                            *reinterpret_cast<const uint4*>(ctile + rloc * CODE_ROW + piece * 16);
-                }
-            }
-        }
-        // every 4th round (and after the last one): the scales of up to 16 groups, 64 bytes per row
-        if ((rd & 3) == 3 || rd == rounds - 1) {
-            const int gbase = (rd & ~3) * WAVES;                     // first group held in this scale tile
-            const int rloc = tid >> 2, q = tid & 3;
-            const int64_t row = row0 + rloc;
-            if (row < M) {
-                const float* src = stile + rloc * SCALE_ROW + q * 4;
-                float* dst = sx + row * ng + gbase + q * 4;
-                if ((ng & 3) == 0) {
-                    if (gbase + q * 4 < ng) *reinterpret_cast<float4*>(dst) = float4{src[0], src[1], src[2], src[3]};
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (gbase + q * 4 + e < ng) dst[e] = src[e];
-                }
-            }
-        }
     };
     for (int rd = 0; rd < rounds; rd += 2) {
         round_body(rd, xa, xb);
@@ -259,7 +219,7 @@ void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
     if (LOWRANK) {
         // D layout of the 32x32 MFMA: lane holds column (lane % 32); register i holds
         // row 8*(i/4) + 4*(lane/32) + (i%4).
-        __syncthreads();                                     // every wave is done with the staging tiles
+        __syncthreads();                                     // every wave is done with inv_lambda in LDS
         float* hpart = reinterpret_cast<float*>(smem_raw);   // [WAVES][64][33]
 #pragma unroll
         for (int b = 0; b < 2; ++b)
@@ -310,7 +270,7 @@ hipError_t launch_quantize(const void* x, int64_t ldx, const float* inv_lambda, 
                            const void* l1p, int64_t M, int K, int r,
                            uint8_t* qx, float* sx, float* h, hipStream_t stream) {
     const unsigned blocks = (unsigned)((M + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
-    size_t lds = (size_t)K * sizeof(float) + 2 * CODE_TILE + 2 * SCALE_TILE;
+    size_t lds = (size_t)K * sizeof(float);
     if (lds < (size_t)HPART_BYTES) lds = HPART_BYTES;
     if (l1p)
         hipLaunchKernelGGL(quantize_kernel<true>, dim3(blocks), dim3(256), lds, stream,

@@ -48,16 +48,20 @@ def check_layer(svdq, oracle, name, x_bits, x_dev, L, DL, rho, n_sample, whole, 
     St = torch.from_numpy(S).cuda()
     xs = np.ascontiguousarray(x_bits[S])
     oq, os_ = oracle.quantize_act(xs, L.inv_lambda, rho)
-    assert np.array_equal(qx[St].cpu().numpy(), oq), f"{name}: codes (row sample)"
-    assert np.array_equal(sx[St].cpu().numpy().view(np.uint32), os_.view(np.uint32)), f"{name}: scales (row sample)"
+    # the library's codes/scales are group-major [K/64, M, ...]; gather the sampled rows and permute
+    gq = qx[:, St].permute(1, 0, 2).reshape(len(S), -1).cpu().numpy()
+    gs = sx[:, St].t().contiguous().cpu().numpy()
+    assert np.array_equal(gq, oq), f"{name}: codes (row sample)"
+    assert np.array_equal(gs.view(np.uint32), os_.view(np.uint32)), f"{name}: scales (row sample)"
     oh = oracle.lowrank_down(xs, L.inv_lambda, L.L1)
     assert rel_fro(h[St].cpu().numpy(), oh) <= 3e-5, f"{name}: h (row sample)"
     progress(f"{name} rho={rho}: codes/scales/h ok on {len(S)} rows")
     if whole:
         fq, fs = oracle.quantize_act(x_bits, L.inv_lambda, rho)
-        assert np.array_equal(sx.cpu().numpy().view(np.uint32), fs.view(np.uint32)), f"{name}: scales (whole buffer)"
-        assert np.array_equal(qx.cpu().numpy(), fq), f"{name}: codes (whole buffer)"
-        del fq, fs
+        wq, ws = svdq.to_token_major(qx, sx)
+        assert np.array_equal(ws.cpu().numpy().view(np.uint32), fs.view(np.uint32)), f"{name}: scales (whole buffer)"
+        assert np.array_equal(wq.cpu().numpy(), fq), f"{name}: codes (whole buffer)"
+        del fq, fs, wq, ws
         progress(f"{name} rho={rho}: whole-buffer codes/scales ok ({M}x{L.K})")
         if whole > 1:
             fh = oracle.lowrank_down(x_bits, L.inv_lambda, L.L1)
@@ -65,7 +69,7 @@ def check_layer(svdq, oracle, name, x_bits, x_dev, L, DL, rho, n_sample, whole, 
             del fh
         for m0 in (0, M - acc_rows):
             acc = svdq.debug_group_acc(qx, DL.wp, L.N, m0, acc_rows).cpu().numpy()
-            want = oracle.group_acc(qx[m0:m0 + acc_rows].cpu().numpy(), L.qw)
+            want = oracle.group_acc(qx[:, m0:m0 + acc_rows].permute(1, 0, 2).reshape(acc_rows, -1).cpu().numpy(), L.qw)
             assert np.array_equal(acc, want), f"{name}: group accumulators rows {m0}.."
             del acc, want
         progress(f"{name}: group accumulators (first rows, ragged last tile) ok")

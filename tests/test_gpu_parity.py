@@ -39,10 +39,18 @@ def run_quant(svdq, x_bits, DL, rho, ldx=None):
     return qx, sx, h
 
 
+def token_major(qx, sx):
+    """The library's group-major codes/scales as token-major numpy arrays (a pure permutation)."""
+    import paper_2605_27003_amd as m
+    q, s = m.to_token_major(qx, sx)
+    return q.cpu().numpy(), s.cpu().numpy()
+
+
 def check_quant(oracle, x_bits, L, rho, qx, sx, h, where):
     oq, os_ = oracle.quantize_act(x_bits, L.inv_lambda, rho)
-    assert np.array_equal(sx.cpu().numpy().view(np.uint32), os_.view(np.uint32)), where + " scales"
-    assert np.array_equal(qx.cpu().numpy(), oq), where + " codes"
+    gq, gs = token_major(qx, sx)
+    assert np.array_equal(gs.view(np.uint32), os_.view(np.uint32)), where + " scales"
+    assert np.array_equal(gq, oq), where + " codes"
     oh = None
     if L.r:
         oh = oracle.lowrank_down(x_bits, L.inv_lambda, L.L1)
@@ -120,8 +128,9 @@ def test_degenerate_groups_and_ties(svdq, oracle):
     for rho in (0.5, 1.0):
         qx, sx, h = run_quant(svdq, xb, DL, rho)
         oq, os_ = oracle.quantize_act(xb, L.inv_lambda, rho)
-        assert np.array_equal(sx.cpu().numpy().view(np.uint32), os_.view(np.uint32))
-        assert np.array_equal(qx.cpu().numpy(), oq)
+        gq, gs = token_major(qx, sx)
+        assert np.array_equal(gs.view(np.uint32), os_.view(np.uint32))
+        assert np.array_equal(gq, oq)
     c = synth.unpack_int4(oracle.quantize_act(xb, L.inv_lambda, 0.5)[0])
     assert c.min() == -8 and c.max() == 7 and not c[0].any()
 
@@ -135,11 +144,12 @@ def test_extreme_codes_accumulators(svdq, oracle):
     sw = np.ones((K // 64, N), np.float32)
     import paper_2605_27003_amd as m
     wp = m.pack_weight(dev(qw), dev(sw))
-    acc = m.debug_group_acc(dev(qx), wp, N, 0, M).cpu().numpy()
+    sx = np.ones((M, K // 64), np.float32)
+    gqx, gsx = m.to_group_major(dev(qx), dev(sx))
+    acc = m.debug_group_acc(gqx, wp, N, 0, M).cpu().numpy()
     assert np.array_equal(acc, oracle.group_acc(qx, qw))
     assert acc.max() == 4096 and acc.min() == -3584
-    sx = np.ones((M, K // 64), np.float32)
-    y = m.linear_w4a4(dev(qx), dev(sx), wp, N, out_dtype=torch.float32).cpu().numpy()
+    y = m.linear_w4a4(gqx, gsx, wp, N, out_dtype=torch.float32).cpu().numpy()
     want = oracle.linear(qx, sx, qw, sw)["y64"]
     assert np.array_equal(y.astype(np.float64), want)
 
@@ -183,8 +193,8 @@ def test_determinism_and_guard_bands(svdq):
     sbuf = torch.full((M * K // 64 + 2 * pad,), -7.0, dtype=torch.float32, device="cuda")
     hbuf = torch.full((M * r + 2 * pad,), -7.0, dtype=torch.float32, device="cuda")
     ybuf = torch.full((M * N + 2 * pad,), -7.0, dtype=torch.bfloat16, device="cuda")
-    qx = qbuf[pad:-pad].view(M, K // 2)
-    sx = sbuf[pad:-pad].view(M, K // 64)
+    qx = qbuf[pad:-pad].view(K // 64, M, 32)
+    sx = sbuf[pad:-pad].view(K // 64, M)
     h = hbuf[pad:-pad].view(M, r)
     y = ybuf[pad:-pad].view(M, N)
     svdq.quantize_act(xt, DL.inv_lambda, 0.8, DL.l1p, r, out=(qx, sx, h))
