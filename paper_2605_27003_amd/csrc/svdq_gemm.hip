@@ -24,11 +24,14 @@
 //
 // Orientation: the MFMA computes the transposed tile D[n][m] (weights are the A
 // operand).  Everything the matrix cores consume reaches them through LDS, staged
-// one stage (two groups) ahead by the whole block, so the compute path has no
-// global-memory waits: activations are unpacked to 16*q bytes while being staged;
-// weights stay 4-bit in LDS (prepacked offline in fragment order) and are unpacked
-// in registers; the bf16 pieces of the weight scales and the correction operands
-// are prepacked offline too.  Block tile 128 x 128, 4 waves of 64 x 64.
+// one stage (two groups) ahead, so the compute path has no global-memory waits.
+// Staging uses the direct global->LDS loads of gfx950 (global_load_lds_dwordx4):
+// no registers, no VALU work and no ds_write for the bulk data.  Codes of both
+// operands stay 4-bit in LDS and are unpacked in registers by the wave that
+// multiplies them; weight fragments, the bf16 pieces of the weight scales and the
+// correction operands are prepacked offline in fragment order; activations arrive
+// group-major from the quantise kernel, which is fragment order already.
+// Block tile 128 x 128, 4 waves of 64 x 64.
 #include "svdq_dev.h"
 #include "svdq_kernels.h"
 
@@ -38,26 +41,36 @@ namespace {
 
 constexpr int BM = 128, BN = 128;
 constexpr int GS = 2;                          // groups per LDS stage
-constexpr int LDS_ROW = 80;                    // 64 operand bytes + 16 pad: conflict-free 16-byte reads
 constexpr uint32_t MAGIC_BITS = 0x40100000u;   // 2.25f
 constexpr float SX_SCALE = 16384.0f;           // 2^14 = 2^22 / 256
 
 struct Stage {
-    uint8_t a[GS][BM * LDS_ROW];               // activations, 16*q per byte, chunk = 2*(odd codes) + 16-byte half
-    uint4 w[GS][BN / 32][64];                  // weight fragments, still 4-bit: [group][n-block][lane]
-    uint2 sxs[GS][BM];                         // {p, p}: m-side operand of the scale-product MFMA (K = 8), p = bf16 hi | lo << 16 of sx*2^14
-    uint2 sfr[GS][BN / 32][32];                // n-side operand of the scale-product MFMA: bf16 {w1, w1, w2, w2}
+    uint4 a[GS][2][BM];                        // activation codes, 4-bit: [group][16-byte half of the group's 32 B][token]
+    uint4 w[GS][BN / 32][64];                  // weight fragments, 4-bit: [group][n-block][lane]
     uint4 cfr[BN / 32][64];                    // n-side operand of the correction MFMA for this pair of groups
+    uint2 sfr[GS][BN / 32][32];                // n-side operand of the scale-product MFMA: bf16 {w1, w1, w2, w2}
+    uint2 sxs[GS][BM];                         // {p, p}: m-side operand of the scale-product MFMA (K = 8), p = bf16 hi | lo << 16 of sx*2^14
 };
 
-__device__ __forceinline__ void unpack_store(uint8_t* dst_row, int sp, uint4 v) {
-    uint4 lo, hi;
-    lo.x = (v.x << 4) & 0xF0F0F0F0u; hi.x = v.x & 0xF0F0F0F0u;
-    lo.y = (v.y << 4) & 0xF0F0F0F0u; hi.y = v.y & 0xF0F0F0F0u;
-    lo.z = (v.z << 4) & 0xF0F0F0F0u; hi.z = v.z & 0xF0F0F0F0u;
-    lo.w = (v.w << 4) & 0xF0F0F0F0u; hi.w = v.w & 0xF0F0F0F0u;
-    *reinterpret_cast<uint4*>(dst_row + sp * 16) = lo;            // k-step 0: even codes
-    *reinterpret_cast<uint4*>(dst_row + (2 + sp) * 16) = hi;      // k-step 1: odd codes
+// One wave-wide direct global->LDS load: lane l moves 16 bytes from its own global address to LDS byte
+// offset lds_off + 16 l.  Written as inline asm so that the compiler does not treat every later LDS
+// read as dependent on it; the issuing code waits (vmcnt) and barriers before anyone reads the data.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_off) {
+    lds_off = __builtin_amdgcn_readfirstlane(lds_off);            // wave-uniform by construction: goes to M0
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+
+// 4-bit codes -> 16*q bytes: even codes of each byte pair (k-step 0) and odd codes (k-step 1)
+__device__ __forceinline__ void unpack16(const uint4 v, int4v& lo, int4v& hi) {
+    const uint32_t pk[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        lo[e] = (int)((pk[e] << 4) & 0xF0F0F0F0u);
+        hi[e] = (int)(pk[e] & 0xF0F0F0F0u);
+    }
 }
 
 // hi | lo << 16 bf16 pieces of v (16 significant bits)
@@ -81,7 +94,7 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
                  const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
                  int64_t M, int64_t ldm, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
                  int mtiles, int ntiles, int64_t dm0, int dmt, int32_t* __restrict__ dacc) {
-    __shared__ __attribute__((aligned(16))) Stage stage[2];
+    __shared__ __attribute__((aligned(16))) Stage stage[3];         // ring: consume s, s+1 landed/landing, s+2 in flight
     __shared__ __attribute__((aligned(16))) uint2 zero_entry;
 
     // XCD-aware tile order: consecutive block ids go round-robin to the 8 XCDs,
@@ -93,7 +106,8 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
     const int mt = (sm * 8 + (rem & 7)) * 8 + xcd;
     if (mt >= mtiles) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // scalar: everything derived from it stays in SGPRs
     const int wm = wave & 1, wn = wave >> 1;
     const int l32 = lane & 31, kh = lane >> 5;
     const int ng = K >> 6;
@@ -102,20 +116,30 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
     const int64_t m0 = (int64_t)mt * BM;
     const int n0 = nt * BN;
 
-    // ---- staging assignment.  Per stage (two groups) a thread moves: 2 x 16 B of activation codes,
-    // 2 x 16 B of weight fragments, 8 B of weight-scale pieces, 16 B of correction operand, one sx.
-    const int srow = tid >> 1, sp = tid & 1;
-    const int64_t arow = (m0 + srow < M) ? (m0 + srow) : (M - 1);
-    const uint8_t* ga = qx + arow * 32 + sp * 16;                 // group-major codes: qx[g][row][32 B]
+    // ---- staging.  Per stage (two groups) the block moves 8 KB of activation codes, 8 KB of weight
+    // fragments, 4 KB of correction operands and 2 KB of weight-scale pieces with direct global->LDS
+    // loads (1 KB per wave instruction, 5-6 instructions per wave), and 256 token scales through registers.
     const int xrow = tid & 127, xg = tid >> 7;                     // sx: threads 0..127 first group, 128..255 second
     const int64_t sxrow = (m0 + xrow < M) ? (m0 + xrow) : (M - 1);
     const float* gsx = DUMP ? nullptr : sx + sxrow;               // group-major scales: sx[g][row]
     const int nbB = n0 >> 5;                                       // first 32-channel block of this tile
-    const int wnb = tid >> 6;                                      // weight fragment: (n-block = tid / 64, lane = tid % 64)
-    const uint4* gw = wfrag + ((size_t)(nbB + wnb) * ng) * 64 + lane;
-    const int snb = (tid >> 5) & 3, sj = tid >> 7;                 // scale pieces: (group = tid / 128, n-block, lane % 32)
-    const uint2* gs = DUMP ? nullptr : sfrag + ((size_t)(nbB + snb) * ng) * 32 + l32;
-    const uint4* gc = DUMP ? nullptr : cfrag + ((size_t)(nbB + wnb) * ngp) * 64 + lane;
+    // activation chunks of this wave: c = 2 wave + {0,1} -> (group j = c/4, half sp = (c/2)%2, 64-row half rh = c%2)
+    const uint8_t* ga[2];
+    int aj[2], asp[2], arh[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = 2 * wave + i;
+        aj[i] = c >> 2; asp[i] = (c >> 1) & 1; arh[i] = c & 1;
+        const int64_t row = m0 + arh[i] * 64 + lane;
+        ga[i] = qx + ((row < M) ? row : (M - 1)) * 32 + asp[i] * 16;       // + g * ldm * 32 per group
+    }
+    // weight chunks of this wave: c = 2 wave + {0,1} -> (group j = c/4, n-block = c%4)
+    const uint4* gw[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) gw[i] = wfrag + ((size_t)(nbB + ((2 * wave + i) & 3)) * ng) * 64 + lane;
+    const uint4* gc = DUMP ? nullptr : cfrag + ((size_t)(nbB + wave) * ngp) * 64 + lane;           // n-block = wave
+    // scale pieces: waves 0 and 1 take group j = wave; lane -> (n-block = lane/16, two entries 2(lane%16), +1)
+    const uint2* gs = DUMP ? nullptr : sfrag + ((size_t)(nbB + (lane >> 4)) * ng) * 32 + 2 * (lane & 15);
 
     float16v y[2][2];                        // [ni][mi]
 #pragma unroll
@@ -134,54 +158,63 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
 #pragma unroll
     for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
 
-    // Plain locals (not a struct): a struct passed around by reference is not split into registers and
-    // ends up in LDS, with a wait for the loads right after they are issued.
-#define SVDQ_STAGE_LOAD(s_)                                                                              \
-    {                                                                                                    \
-        const int ga_ = ((s_) * GS < ng) ? (s_) * GS : (ng - 1);                                         \
-        const int gb_ = ((s_) * GS + 1 < ng) ? (s_) * GS + 1 : (ng - 1);   /* odd tail: re-read the last group */ \
-        va0 = *reinterpret_cast<const uint4*>(ga + (size_t)ga_ * ldm * 32);                              \
-        va1 = *reinterpret_cast<const uint4*>(ga + (size_t)gb_ * ldm * 32);                              \
-        vw0 = gw[(size_t)ga_ * 64];                                                                      \
-        vw1 = gw[(size_t)gb_ * 64];                                                                      \
-        if (!DUMP) {                                                                                     \
-            const int gsj_ = ((s_) * GS + sj < ng) ? (s_) * GS + sj : (ng - 1);                          \
-            vs = gs[(size_t)gsj_ * 32];                                                                  \
-            vc = gc[(size_t)(s_) * 64];                                                                  \
-            const int gx_ = (s_) * GS + xg;                                                              \
-            sc = gsx[(size_t)(gx_ < ng ? gx_ : ng - 1) * ldm];                                           \
-            sc_live = gx_ < ng;        /* applied at store time: using sc here would wait for the load */ \
-        }                                                                                                \
-    }
-#define SVDQ_STAGE_STORE(st_)                                                                            \
-    {                                                                                                    \
-        unpack_store((st_).a[0] + srow * LDS_ROW, sp, va0);                                              \
-        unpack_store((st_).a[1] + srow * LDS_ROW, sp, va1);                                              \
-        (st_).w[0][wnb][lane] = vw0;                                                                     \
-        (st_).w[1][wnb][lane] = vw1;                                                                     \
-        if (!DUMP) {                                                                                     \
-            (st_).sfr[sj][snb][l32] = vs;                                                                \
-            (st_).cfr[wnb][lane] = vc;                                                                   \
-            const uint32_t p_ = sc_live ? split_bf16(sc * SX_SCALE) : 0u;                                             \
-            (st_).sxs[xg][xrow] = uint2{p_, p_};                                                         \
-        }                                                                                                \
-    }
-    uint4 va0, va1, vw0, vw1, vc = {0u, 0u, 0u, 0u};
-    uint2 vs = {0u, 0u};
     float sc = 0.0f;
     bool sc_live = false;
+    const int ndma = DUMP ? 4 : (wave < 2 ? 6 : 5);                 // direct-to-LDS loads this wave issues per stage
+    // scale of this thread's (group, token) of stage s: through a register, issued BEFORE the bulk loads
+    auto scale_issue = [&](const int s) {
+        if (!DUMP) {
+            const int gx = s * GS + xg;
+            sc = gsx[(size_t)(gx < ng ? gx : ng - 1) * ldm];
+            sc_live = gx < ng;                   // applied at store time: using sc here would wait for the load
+        }
+    };
+    auto stage_issue = [&](const int s, Stage& st) {
+        const int gj[2] = {(s * GS < ng) ? s * GS : ng - 1, (s * GS + 1 < ng) ? s * GS + 1 : ng - 1};   // odd tail: re-read
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            dma16(ga[i] + (size_t)gj[aj[i]] * ldm * 32, lds_offset(&st.a[aj[i]][asp[i]][arh[i] * 64]));
+            dma16(gw[i] + (size_t)gj[(2 * wave + i) >> 2] * 64, lds_offset(&st.w[(2 * wave + i) >> 2][(2 * wave + i) & 3][0]));
+        }
+        if (!DUMP) {
+            dma16(gc + (size_t)s * 64, lds_offset(&st.cfr[wave][0]));
+            if (wave < 2) dma16(gs + (size_t)gj[wave] * 32, lds_offset(&st.sfr[wave][0][0]));
+        }
+    };
+    auto scale_store = [&](Stage& st) {
+        if (!DUMP) {
+            const uint32_t p = sc_live ? split_bf16(sc * SX_SCALE) : 0u;
+            st.sxs[xg][xrow] = uint2{p, p};
+        }
+    };
+    // wait until at most `n` of this wave's vector-memory loads are outstanding (they complete in order)
+    auto wait_loads = [&](const int n) {
+        if (n == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (n == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else if (n == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    };
 
-    // prologue: stage 0
-    SVDQ_STAGE_LOAD(0);
-    SVDQ_STAGE_STORE(stage[0]);
+    // prologue: stage 0 completely, bulk loads of stage 1 in flight
+    scale_issue(0);
+    stage_issue(0, stage[0]);
+    if (nstages > 1) stage_issue(1, stage[1]);
+    wait_loads(nstages > 1 ? ndma : 0);
+    scale_store(stage[0]);
     if (tid == 0) zero_entry = uint2{0u, 0u};
     __syncthreads();
 
+    int cur_i = 0;                                                  // ring index of the stage being consumed
     for (int s = 0; s < nstages; ++s) {
-        const Stage& cur = stage[s & 1];
-        Stage& nxt = stage[(s + 1) & 1];
-        const bool more = (s + 1 < nstages);
-        if (more) SVDQ_STAGE_LOAD(s + 1);
+        const int nxt_i = (cur_i == 2) ? 0 : cur_i + 1;
+        const int nn_i = (nxt_i == 2) ? 0 : nxt_i + 1;
+        const Stage& cur = stage[cur_i];
+        Stage& nxt = stage[nxt_i];
+        const bool more = (s + 1 < nstages), more2 = (s + 2 < nstages);
+        // order matters: the token scale of stage s+1 first, then the bulk loads of stage s+2, so that the
+        // wait at the end of this stage (everything but the last ndma loads) covers all of stage s+1
+        if (more) scale_issue(s + 1);
+        if (more2) stage_issue(s + 2, stage[nn_i]);
 
 #pragma unroll
         for (int j = 0; j < GS; ++j) {
@@ -190,16 +223,13 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
 
             // every LDS operand of this group is requested up front (and the scheduler may not sink the
             // reads next to their uses): LDS latency is then paid once per group, not once per MFMA
-            int4v xf[2][2];
+            uint4 xpk[2], wpk[2], cn[2];
             uint2 sxs[2], sfr[2];
-            uint4 wpk[2], cn[2];
             uint32_t cp_[2];
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi) {
                 const int rrow = wm * 64 + mi * 32 + l32;
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-                    xf[mi][ks] = *reinterpret_cast<const int4v*>(cur.a[j] + rrow * LDS_ROW + (2 * ks + kh) * 16);
+                xpk[mi] = cur.a[j][kh][rrow];
                 if (!DUMP) {
                     const uint2* pe = kh ? &zero_entry : &cur.sxs[j][rrow];
                     sxs[mi] = *pe;
@@ -229,20 +259,18 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
                 }
             }
 
+            // int4 -> 16*q bytes, in registers
+            int4v xlo[2], xhi[2];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) unpack16(xpk[mi], xlo[mi], xhi[mi]);
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni) {
-                // int4 -> 16*q bytes, in registers (this wave's 32 output channels)
                 int4v wlo, whi;
-                const uint32_t pk[4] = {wpk[ni].x, wpk[ni].y, wpk[ni].z, wpk[ni].w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    wlo[e] = (int)((pk[e] << 4) & 0xF0F0F0F0u);
-                    whi[e] = (int)(pk[e] & 0xF0F0F0F0u);
-                }
+                unpack16(wpk[ni], wlo, whi);
 #pragma unroll
                 for (int mi = 0; mi < 2; ++mi) {
-                    int16v acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wlo, xf[mi][0], magic, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(whi, xf[mi][1], acc, 0, 0, 0);
+                    int16v acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wlo, xlo[mi], magic, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(whi, xhi[mi], acc, 0, 0, 0);
                     if (DUMP) {
                         const int64_t m = m0 + wm * 64 + mi * 32 + l32;
                         if (m >= dm0 && m < dm0 + dmt && m < M) {
@@ -263,12 +291,14 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
             }
         }
 
-        if (more) SVDQ_STAGE_STORE(nxt);
+        if (more) {
+            wait_loads(more2 ? ndma : 0);
+            scale_store(nxt);
+        }
         __syncthreads();
+        cur_i = nxt_i;
     }
 
-#undef SVDQ_STAGE_LOAD
-#undef SVDQ_STAGE_STORE
     if (DUMP) return;
 
     // ---- epilogue (c): low-rank up-projection on the bf16 matrix cores, bias, store
