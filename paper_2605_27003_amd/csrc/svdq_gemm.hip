@@ -247,18 +247,6 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
             }
             __builtin_amdgcn_sched_barrier(0);
 
-            if (!DUMP && j == 0) {
-                // y -= 2.25 * (S_g + S_{g+1}) for the four tiles, before the two groups add it back
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi) {
-                    const uint4 cm = {cp_[mi], cp_[mi], cp_[mi], cp_[mi]};
-#pragma unroll
-                    for (int ni = 0; ni < 2; ++ni)
-                        y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cn[ni]),
-                                                                            __builtin_bit_cast(bf16x8, cm), y[ni][mi], 0, 0, 0);
-                }
-            }
-
             // int4 -> 16*q bytes, in registers
             int4v xlo[2], xhi[2];
 #pragma unroll
@@ -289,6 +277,19 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
                     }
                 }
             }
+            if (!DUMP && j == 0) {
+                // y -= 2.25 * (S_g + S_{g+1}) for the four tiles, between the two groups that add it: y then strays
+                // from the true partial sum by at most 2.25 * S in either direction
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) {
+                    const uint4 cm = {cp_[mi], cp_[mi], cp_[mi], cp_[mi]};
+#pragma unroll
+                    for (int ni = 0; ni < 2; ++ni)
+                        y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cn[ni]),
+                                                                            __builtin_bit_cast(bf16x8, cm), y[ni][mi], 0, 0, 0);
+                }
+            }
+
         }
 
         if (more) {
