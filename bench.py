@@ -21,6 +21,19 @@ INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8 matrix peak
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E
 
 
+def measured_traffic(workload_name, kernel):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload (FETCH_SIZE + WRITE_SIZE,
+    each scaled by what the counter reads for a copy of known size), or None when there is no summary."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"{workload_name.split(':')[0]}_hbm_traffic.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(rf"^traffic_bytes_per_launch\s+{kernel}\s+(\d+)", text, re.M)
+    return int(m.group(1)) if m else None
+
+
 def cpu_baseline(w, L, rows, seed=7):
     """The CPU oracle as it stands, timed on a row sample (rows are independent, so the sample is exact)."""
     import numpy as np
@@ -49,10 +62,11 @@ def cpu_baseline(w, L, rows, seed=7):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed steps; the clocks need some tens of launches after idle to settle")
     ap.add_argument("--workload", type=int, default=1, help="index into the five configurations (default: the metric's)")
-    ap.add_argument("--cpu-rows", type=int, default=4096, help="token rows of the CPU-oracle baseline sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=12288, help="token rows of the CPU-oracle baseline sample (0 = skip)")
     ap.add_argument("--xsets", type=int, default=3, help="input buffer sets rotated so caches cannot hold the working set")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -124,11 +138,13 @@ def main():
                    "step": "svdq_quantize_act + svdq_linear_w4a4", "input_sets": len(xs)},
         "roofline": {"kernel": "svdq_linear_w4a4 (gemm_kernel)", "bound": "mfma",
                      "achieved": gemm_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": gemm_tops / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                     "frac": gemm_tops / INT8_MFMA_PEAK_TOPS,
+                     "traffic": measured_traffic(w.name, "gemm_kernel"),
                      "avg_ms": float(tg.mean()), "min_ms": float(tg.min())},
         "roofline_quantize": {"kernel": "svdq_quantize_act (quantize_kernel)", "bound": "hbm",
                               "achieved": quant_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": quant_gbs / HBM_PEAK_GBS, "traffic": None,
+                              "frac": quant_gbs / HBM_PEAK_GBS,
+                              "traffic": measured_traffic(w.name, "quantize_kernel"),
                               "algorithmic_bytes": bytes_q, "avg_ms": float(tq.mean()), "min_ms": float(tq.min())},
     }
     del xs, ysets

@@ -155,6 +155,15 @@ int svdq_lowrank(int mode, const void* x_bf16, int64_t ldx, const float* inv_lam
 int svdq_debug_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int N, int K,
                          int64_t m0, int mt, int32_t* acc, void* stream);
 
+/*
+ * Test hook: the scalar part of kernel (a)'s chain, eq. 8-9, evaluated by the
+ * kernel's own device functions on n given group magnitudes a[i] >= 0:
+ *   s[i]   = (rho * a[i]) / 7, or 0 when that is not a normal number
+ *   inv[i] = 1 / s[i], or 0 when s[i] == 0
+ * each required to equal the single IEEE binary32 operation.  n <= 2^31.
+ */
+int svdq_debug_scale_chain(const float* a, float rho, int64_t n, float* s, float* inv, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -7,7 +7,7 @@ store) runs in the HIP kernels.  There is no CPU fallback: if the library is
 missing or the device is not gfx950 the calls raise.
 """
 from .binding import (  # noqa: F401
-    SvdqError, alpha_lookup, debug_group_acc, linear_w4a4, load_library, lowrank,
+    SvdqError, alpha_lookup, debug_group_acc, debug_scale_chain, linear_w4a4, load_library, lowrank,
     pack_lowrank_down, pack_weight, packed_l1_bytes, packed_weight_bytes, quantize_act, version,
     to_group_major, to_token_major,
     W4A4Linear,

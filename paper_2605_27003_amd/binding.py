@@ -23,6 +23,7 @@ EXPORTS = {
     "svdq_linear_w4a4": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _i32, _vp]),
     "svdq_lowrank": (_i32, [_i32, _vp, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _i64, _vp]),
     "svdq_debug_group_acc": (_i32, [_vp, _vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp]),
+    "svdq_debug_scale_chain": (_i32, [_vp, _f32, _i64, _vp, _vp, _vp]),
 }
 
 
@@ -171,6 +172,16 @@ def debug_group_acc(qx, w_packed, N, m0, mt):
     _check(load_library().svdq_debug_group_acc(_ptr(qx), _ptr(w_packed), M, N, K, m0, mt, _ptr(acc), _stream()),
            "svdq_debug_group_acc")
     return acc
+
+
+def debug_scale_chain(a, rho):
+    """(s, 1/s) of eq. 8-9 for group magnitudes a (float32 device tensor), from the kernel's device functions."""
+    a = a.contiguous()
+    s = torch.empty_like(a)
+    inv = torch.empty_like(a)
+    _check(load_library().svdq_debug_scale_chain(_ptr(a), float(rho), a.numel(), _ptr(s), _ptr(inv), _stream()),
+           "svdq_debug_scale_chain")
+    return s, inv
 
 
 class W4A4Linear:

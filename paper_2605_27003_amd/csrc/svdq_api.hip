@@ -147,4 +147,12 @@ int svdq_debug_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int
     return hip_status(svdq::launch_group_acc(qx, w_packed, M, N, K, m0, mt, acc, (hipStream_t)stream));
 }
 
+int svdq_debug_scale_chain(const float* a, float rho, int64_t n, float* s, float* inv, void* stream) {
+    if (!a || !s || !inv || n < 0 || n > (int64_t)1 << 31) return SVDQ_ERR_INVALID_ARG;
+    if (!(rho > 0.0f) || !(rho <= 1.0f)) return SVDQ_ERR_INVALID_ARG;
+    if (n == 0) return SVDQ_OK;
+    if (int e = check_arch()) return e;
+    return hip_status(svdq::launch_scale_chain(a, rho, n, s, inv, (hipStream_t)stream));
+}
+
 }  // extern "C"

@@ -11,6 +11,7 @@ hipError_t launch_quantize(const void* x, int64_t ldx, const float* inv_lambda, 
                            const void* l1p, int64_t M, int K, int r,
                            uint8_t* qx, float* sx, float* h, hipStream_t stream);
 hipError_t launch_pack_l1(const void* L1, const float* inv_lambda, int K, int r, void* out, hipStream_t stream);
+hipError_t launch_scale_chain(const float* a, float rho, int64_t n, float* s, float* inv, hipStream_t stream);
 inline size_t packed_l1_bytes(int K) { return (size_t)(K / 64) * 4 * 2 * 64 * 16; }
 
 // svdq_gemm.hip

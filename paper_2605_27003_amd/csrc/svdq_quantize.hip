@@ -48,8 +48,8 @@ __device__ __forceinline__ float div7(float t) {
 }
 
 // RN(1/s) from v_rcp_f32 (1 ulp) and one FMA Newton step.  Equal to IEEE division for every mantissa
-// on gfx950 as long as 1/s is a normal number (checked exhaustively on the GPU, test_gpu_parity);
-// huge s takes the IEEE sequence.
+// on gfx950 as long as 1/s is a normal number (the GPU tests sweep every mantissa through
+// scale_chain_kernel below); huge s takes the IEEE sequence.
 __device__ __forceinline__ float recip_rn(float s) {
     float r0 = __builtin_amdgcn_rcpf(s);
     float e = __builtin_fmaf(-s, r0, 1.0f);
@@ -264,7 +264,26 @@ __global__ void pack_l1_kernel(const uint16_t* __restrict__ L1, const float* __r
     }
 }
 
+// Test hook: the scalar part of the quantiser chain (eq. 8-9) on arbitrary inputs, through the same
+// device functions the quantise kernel uses.
+__global__ void scale_chain_kernel(const float* __restrict__ a, float rho, int64_t n,
+                                   float* __restrict__ s_out, float* __restrict__ inv_out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = div7(__fmul_rn(rho, a[i]));
+    const bool live = s >= 1.17549435e-38f;
+    s = live ? s : 0.0f;
+    s_out[i] = s;
+    inv_out[i] = live ? recip_rn(s) : 0.0f;
+}
+
 }  // namespace
+
+hipError_t launch_scale_chain(const float* a, float rho, int64_t n, float* s, float* inv, hipStream_t stream) {
+    const int64_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(scale_chain_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a, rho, n, s, inv);
+    return hipGetLastError();
+}
 
 hipError_t launch_quantize(const void* x, int64_t ldx, const float* inv_lambda, float rho,
                            const void* l1p, int64_t M, int K, int r,

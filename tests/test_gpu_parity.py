@@ -207,3 +207,24 @@ def test_determinism_and_guard_bands(svdq):
         assert torch.equal(a, b)
     for buf, val in ((qbuf, 0xAB), (sbuf, -7.0), (hbuf, -7.0), (ybuf, -7.0)):
         assert torch.all(buf[:pad] == val) and torch.all(buf[-pad:] == val)
+
+
+@pytest.mark.parametrize("rho", [1.0, 0.9, 0.7])
+def test_scale_chain_every_mantissa(svdq, rho):
+    """eq. 8-9 scalars: the kernel's division by q_max = 7 and its reciprocal of the scale are formed from a
+    multiply plus FMA corrections, not from division instructions.  They must equal the IEEE binary32
+    operations (numpy float32 arithmetic here) for every one of the 2^23 mantissas, at exponents spread over
+    the whole range, including the hand-over to the denormal rule (scale below 2^-126 -> 0)."""
+    mant = np.arange(1 << 23, dtype=np.uint32)
+    rho32 = np.float32(rho)
+    for e in (-126, -124, -123, -101, -99, -64, -13, -1, 0, 1, 2, 17, 64, 100, 122, 125, 127):
+        a = ((np.uint32(e + 127) << np.uint32(23)) | mant).view(np.float32)
+        with np.errstate(divide="ignore", under="ignore"):
+            s_ref = (rho32 * a) / np.float32(7.0)
+            s_ref = np.where(s_ref >= np.float32(2.0 ** -126), s_ref, np.float32(0.0)).astype(np.float32)
+            inv_ref = np.where(s_ref > 0, np.float32(1.0) / np.where(s_ref > 0, s_ref, np.float32(1.0)),
+                               np.float32(0.0)).astype(np.float32)
+        s, inv = svdq.debug_scale_chain(torch.from_numpy(a).cuda(), rho)
+        torch.cuda.synchronize()
+        assert np.array_equal(s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32)), (e, "scale")
+        assert np.array_equal(inv.cpu().numpy().view(np.uint32), inv_ref.view(np.uint32)), (e, "reciprocal")
