@@ -39,28 +39,51 @@ namespace svdq {
 
 namespace {
 
+template <int V> struct IC { static constexpr int value = V; };
+
 constexpr int BM = 128, BN = 128;
 constexpr int GS = 2;                          // groups per LDS stage
 constexpr uint32_t MAGIC_BITS = 0x40100000u;   // 2.25f
 constexpr float SX_SCALE = 16384.0f;           // 2^14 = 2^22 / 256
 
-struct Stage {
-    uint4 a[GS][2][BM];                        // activation codes, 4-bit: [group][16-byte half of the group's 32 B][token]
-    uint4 w[GS][BN / 32][64];                  // weight fragments, 4-bit: [group][n-block][lane]
-    uint4 cfr[BN / 32][64];                    // n-side operand of the correction MFMA for this pair of groups
-    uint2 sfr[GS][BN / 32][32];                // n-side operand of the scale-product MFMA: bf16 {w1, w1, w2, w2}
-    uint2 sxs[GS][BM];                         // {p, p}: m-side operand of the scale-product MFMA (K = 8), p = bf16 hi | lo << 16 of sx*2^14
-};
+// One LDS ring slot = one stage = two groups of a 128 x 128 block tile (byte offsets inside the slot)
+constexpr uint32_t OFF_A = 0;          // activation codes, 4-bit: [group][16-byte half of the group's 32 B][token] x 16 B
+constexpr uint32_t OFF_W = 8192;       // weight fragments, 4-bit: [group][n-block][lane] x 16 B
+constexpr uint32_t OFF_CFR = 16384;    // n-side operand of the correction MFMA for this pair of groups: [n-block][lane] x 16 B
+constexpr uint32_t OFF_SFR = 20480;    // n-side operand of the scale-product MFMA: [group][n-block][lane] x 8 B (lanes 32..63 zero)
+constexpr uint32_t OFF_SXS = 24576;    // {p, p} per token: m-side operand of the scale-product MFMA: [group][token] x 8 B
+constexpr uint32_t STAGE_BYTES = 26624;
+constexpr int NSLOTS = 3;
 
-// One wave-wide direct global->LDS load: lane l moves 16 bytes from its own global address to LDS byte
-// offset lds_off + 16 l.  Written as inline asm so that the compiler does not treat every later LDS
-// read as dependent on it; the issuing code waits (vmcnt) and barriers before anyone reads the data.
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_off) {
-    lds_off = __builtin_amdgcn_readfirstlane(lds_off);            // wave-uniform by construction: goes to M0
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory");
+typedef __attribute__((address_space(3))) uint8_t lds_byte;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 lds_read16(uint32_t off) {
+    const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>((lds_byte*)(uintptr_t)off);
+    return uint4{v.x, v.y, v.z, v.w};
 }
-__device__ __forceinline__ uint32_t lds_offset(const void* p) {
-    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+__device__ __forceinline__ uint2 lds_read8(uint32_t off) {
+    const u32x2 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x2*>((lds_byte*)(uintptr_t)off);
+    return uint2{v.x, v.y};
+}
+__device__ __forceinline__ uint32_t lds_read4(uint32_t off) {
+    return *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>((lds_byte*)(uintptr_t)off);
+}
+__device__ __forceinline__ void lds_write8(uint32_t off, uint2 v) {
+    const u32x2 t = {v.x, v.y};
+    *reinterpret_cast<__attribute__((address_space(3))) u32x2*>((lds_byte*)(uintptr_t)off) = t;
+}
+
+// One wave-wide direct global->LDS load: lane l moves 16 bytes from global address sbase + voff(l) to LDS
+// byte offset lds_off + 16 l.  sbase and lds_off are wave-uniform (scalar registers), so a transfer costs
+// no vector-ALU work.  Written as inline asm so that the compiler does not treat every later LDS read as
+// dependent on it; the issuing code waits (vmcnt) and barriers before anyone reads the data.
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_off) {
+    const uint64_t a = (uint64_t)(uintptr_t)sbase;
+    const uint64_t sa = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32)) << 32) |
+                        (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    lds_off = __builtin_amdgcn_readfirstlane(lds_off);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sa), "s"(lds_off) : "memory");
 }
 
 // 4-bit codes -> 16*q bytes: even codes of each byte pair (k-step 0) and odd codes (k-step 1)
@@ -82,7 +105,7 @@ __device__ __forceinline__ uint32_t split_bf16(float v) {
 
 // sizes of the packed weight regions (bytes)
 __host__ __device__ inline size_t wfrag_bytes(int N, int K) { return (size_t)N * (K / 2); }
-__host__ __device__ inline size_t sfrag_bytes(int N, int K) { return (size_t)(N / 32) * (K / 64) * 256; }
+__host__ __device__ inline size_t sfrag_bytes(int N, int K) { return (size_t)(N / 32) * (K / 64) * 512; }
 __host__ __device__ inline size_t cfrag_bytes(int N, int K) { return (size_t)(N / 32) * ((K / 64 + 1) / 2) * 1024; }
 
 // DUMP = false: the layer.  DUMP = true: write the int32 group accumulators of
@@ -94,8 +117,7 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
                  const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
                  int64_t M, int64_t ldm, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
                  int mtiles, int ntiles, int64_t dm0, int dmt, int32_t* __restrict__ dacc) {
-    __shared__ __attribute__((aligned(16))) Stage stage[3];         // ring: consume s, s+1 landed/landing, s+2 in flight
-    __shared__ __attribute__((aligned(16))) uint2 zero_entry;
+    __shared__ __attribute__((aligned(16))) uint8_t ring[NSLOTS * STAGE_BYTES];   // slot of stage s: s % 3
 
     // XCD-aware tile order: consecutive block ids go round-robin to the 8 XCDs,
     // so give each XCD its own token tiles and walk them 8 at a time across n.
@@ -115,31 +137,63 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
     const int nstages = ngp;
     const int64_t m0 = (int64_t)mt * BM;
     const int n0 = nt * BN;
-
-    // ---- staging.  Per stage (two groups) the block moves 8 KB of activation codes, 8 KB of weight
-    // fragments, 4 KB of correction operands and 2 KB of weight-scale pieces with direct global->LDS
-    // loads (1 KB per wave instruction, 5-6 instructions per wave), and 256 token scales through registers.
-    const int xrow = tid & 127, xg = tid >> 7;                     // sx: threads 0..127 first group, 128..255 second
-    const int64_t sxrow = (m0 + xrow < M) ? (m0 + xrow) : (M - 1);
-    const float* gsx = DUMP ? nullptr : sx + sxrow;               // group-major scales: sx[g][row]
     const int nbB = n0 >> 5;                                       // first 32-channel block of this tile
-    // activation chunks of this wave: c = 2 wave + {0,1} -> (group j = c/4, half sp = (c/2)%2, 64-row half rh = c%2)
-    const uint8_t* ga[2];
-    int aj[2], asp[2], arh[2];
+    const uint32_t ring0 = (uint32_t)(uintptr_t)(lds_byte*)ring;
+
+    // ---- staging.  Per stage (two groups) every wave issues six direct global->LDS loads of 1 KB: two of
+    // activation codes, two of weight fragments, one of correction operands, one of weight-scale pieces
+    // (NDMA = 4 without the scale data); the 256 token scales go through registers.  Global addresses are
+    // a wave-uniform base (advanced per stage on the scalar unit) plus a per-lane offset fixed for the kernel.
+    constexpr int NDMA = DUMP ? 4 : 6;
+    uint32_t va[2], lds_a[2], lds_w[2];        // activation chunks c = 2 wave + i -> (group j = c/4, half sp = (c/2)%2, 64-row half rh = c%2)
+    int cj[2];                                 // weight chunks      c = 2 wave + i -> (group j = c/4, n-block = c%4)
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int c = 2 * wave + i;
-        aj[i] = c >> 2; asp[i] = (c >> 1) & 1; arh[i] = c & 1;
-        const int64_t row = m0 + arh[i] * 64 + lane;
-        ga[i] = qx + ((row < M) ? row : (M - 1)) * 32 + asp[i] * 16;       // + g * ldm * 32 per group
+        const int sp = (c >> 1) & 1, rh = c & 1;
+        cj[i] = c >> 2;
+        const int64_t row = m0 + rh * 64 + lane;
+        va[i] = (uint32_t)(((row < M) ? row : (M - 1)) * 32 + sp * 16);
+        lds_a[i] = OFF_A + ((cj[i] * 2 + sp) * BM + rh * 64) * 16;
+        lds_w[i] = OFF_W + ((cj[i] * 4 + (c & 3)) * 64) * 16;
     }
-    // weight chunks of this wave: c = 2 wave + {0,1} -> (group j = c/4, n-block = c%4)
-    const uint4* gw[2];
+    const uint32_t vl16 = lane * 16;
+    const uint32_t vsf = (uint32_t)(kh * ng * 512 + l32 * 16);       // scale pieces: lanes 0..31 one n-block, 32..63 the next
+    const int sfj = wave >> 1, sfp = wave & 1;                        // this wave's (group, pair of n-blocks) of the scale pieces
+    const int xrow = tid & 127;                                       // token scales: waves 0,1 first group, waves 2,3 second
+    const int xg = wave >> 1;
+    const int64_t sxrow = (m0 + xrow < M) ? (m0 + xrow) : (M - 1);
+
+    auto stage_issue = [&](const int s) {
+        const uint32_t slot = ring0 + (uint32_t)(s % NSLOTS) * STAGE_BYTES;
+        const int gj[2] = {(2 * s < ng) ? 2 * s : ng - 1, (2 * s + 1 < ng) ? 2 * s + 1 : ng - 1};   // odd tail: re-read
 #pragma unroll
-    for (int i = 0; i < 2; ++i) gw[i] = wfrag + ((size_t)(nbB + ((2 * wave + i) & 3)) * ng) * 64 + lane;
-    const uint4* gc = DUMP ? nullptr : cfrag + ((size_t)(nbB + wave) * ngp) * 64 + lane;           // n-block = wave
-    // scale pieces: waves 0 and 1 take group j = wave; lane -> (n-block = lane/16, two entries 2(lane%16), +1)
-    const uint2* gs = DUMP ? nullptr : sfrag + ((size_t)(nbB + (lane >> 4)) * ng) * 32 + 2 * (lane & 15);
+        for (int i = 0; i < 2; ++i) {
+            dma16(qx + (size_t)gj[cj[i]] * ldm * 32, va[i], slot + lds_a[i]);
+            dma16(wfrag + ((size_t)(nbB + ((2 * wave + i) & 3)) * ng + gj[cj[i]]) * 64, vl16, slot + lds_w[i]);
+        }
+        if (!DUMP) {
+            dma16(cfrag + ((size_t)(nbB + wave) * ngp + s) * 64, vl16, slot + OFF_CFR + wave * 1024);
+            dma16(sfrag + ((size_t)(nbB + 2 * sfp) * ng + gj[sfj]) * 64, vsf, slot + OFF_SFR + (sfj * 4 + 2 * sfp) * 512);
+        }
+    };
+    // token scale of this thread's (group, token) of stage s, through a register
+    auto scale_load = [&](const int s) -> float {
+        const int gx = 2 * s + xg;
+        return sx[(size_t)(gx < ng ? gx : ng - 1) * ldm + sxrow];
+    };
+    auto scale_store = [&](const int s, const float sc, const bool exists = false) {
+        const uint32_t p = (exists || 2 * s + xg < ng) ? split_bf16(sc * SX_SCALE) : 0u;
+        lds_write8(ring0 + (uint32_t)(s % NSLOTS) * STAGE_BYTES + OFF_SXS + (xg * BM + xrow) * 8, uint2{p, p});
+    };
+
+    // per-lane LDS read offsets inside a slot
+    const uint32_t rd_a = OFF_A + (kh * BM + wm * 64 + l32) * 16;      // + group 4096 + mi 512
+    const uint32_t rd_w = OFF_W + (wn * 2 * 64 + lane) * 16;           // + group 4096 + ni 1024
+    const uint32_t rd_cn = OFF_CFR + (wn * 2 * 64 + lane) * 16;        // + ni 1024
+    const uint32_t rd_sf = OFF_SFR + (wn * 2 * 64 + lane) * 8;         // + group 2048 + ni 512
+    const uint32_t rd_sx = OFF_SXS + (wm * 64 + l32) * 8;              // + group 1024 + mi 256
+    const uint32_t rd_cp = OFF_SXS + (kh * BM + wm * 64 + l32) * 8;    // + mi 256: lanes 0..31 group g, 32..63 group g+1
 
     float16v y[2][2];                        // [ni][mi]
 #pragma unroll
@@ -158,147 +212,170 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
 #pragma unroll
     for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
 
+    // prologue: stages 0..2 requested, stage 0 landed and visible, MFMA operands of group 0 requested
     float sc = 0.0f;
-    bool sc_live = false;
-    const int ndma = DUMP ? 4 : (wave < 2 ? 6 : 5);                 // direct-to-LDS loads this wave issues per stage
-    // scale of this thread's (group, token) of stage s: through a register, issued BEFORE the bulk loads
-    auto scale_issue = [&](const int s) {
+    {
+        float sc0 = 0.0f;
         if (!DUMP) {
-            const int gx = s * GS + xg;
-            sc = gsx[(size_t)(gx < ng ? gx : ng - 1) * ldm];
-            sc_live = gx < ng;                   // applied at store time: using sc here would wait for the load
+            sc0 = scale_load(0);
+            if (nstages > 1) sc = scale_load(1);
         }
-    };
-    auto stage_issue = [&](const int s, Stage& st) {
-        const int gj[2] = {(s * GS < ng) ? s * GS : ng - 1, (s * GS + 1 < ng) ? s * GS + 1 : ng - 1};   // odd tail: re-read
+        stage_issue(0);
+        if (nstages > 1) stage_issue(1);
+        if (nstages > 2) stage_issue(2);
+        if (nstages > 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
+        else if (nstages > 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (!DUMP) scale_store(0, sc0);
+        __syncthreads();
+    }
+    // ---- main loop.  One step = one 32 x 32 tile of one group: its two integer MFMAs and its scale-product
+    // MFMA are issued, and while they run the vector ALU finishes the PREVIOUS tile (16 FMAs on results that
+    // completed a step ago) and unpacks operands.  All LDS operands are requested one group ahead.
+    uint4 xpk[2], wpk[2];                      // 4-bit MFMA operands of the next group to start
+    uint2 sxs[2], sfr[2];                      // scale-product operands of the same group
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            dma16(ga[i] + (size_t)gj[aj[i]] * ldm * 32, lds_offset(&st.a[aj[i]][asp[i]][arh[i] * 64]));
-            dma16(gw[i] + (size_t)gj[(2 * wave + i) >> 2] * 64, lds_offset(&st.w[(2 * wave + i) >> 2][(2 * wave + i) & 3][0]));
-        }
-        if (!DUMP) {
-            dma16(gc + (size_t)s * 64, lds_offset(&st.cfr[wave][0]));
-            if (wave < 2) dma16(gs + (size_t)gj[wave] * 32, lds_offset(&st.sfr[wave][0][0]));
-        }
-    };
-    auto scale_store = [&](Stage& st) {
-        if (!DUMP) {
-            const uint32_t p = sc_live ? split_bf16(sc * SX_SCALE) : 0u;
-            st.sxs[xg][xrow] = uint2{p, p};
-        }
-    };
-    // wait until at most `n` of this wave's vector-memory loads are outstanding (they complete in order)
-    auto wait_loads = [&](const int n) {
-        if (n == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else if (n == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else if (n == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-    };
-
-    // prologue: stage 0 completely, bulk loads of stage 1 in flight
-    scale_issue(0);
-    stage_issue(0, stage[0]);
-    if (nstages > 1) stage_issue(1, stage[1]);
-    wait_loads(nstages > 1 ? ndma : 0);
-    scale_store(stage[0]);
-    if (tid == 0) zero_entry = uint2{0u, 0u};
-    __syncthreads();
-
-    int cur_i = 0;                                                  // ring index of the stage being consumed
-    for (int s = 0; s < nstages; ++s) {
-        const int nxt_i = (cur_i == 2) ? 0 : cur_i + 1;
-        const int nn_i = (nxt_i == 2) ? 0 : nxt_i + 1;
-        const Stage& cur = stage[cur_i];
-        Stage& nxt = stage[nxt_i];
-        const bool more = (s + 1 < nstages), more2 = (s + 2 < nstages);
-        // order matters: the token scale of stage s+1 first, then the bulk loads of stage s+2, so that the
-        // wait at the end of this stage (everything but the last ndma loads) covers all of stage s+1
-        if (more) scale_issue(s + 1);
-        if (more2) stage_issue(s + 2, stage[nn_i]);
-
+    for (int mi = 0; mi < 2; ++mi) {
+        xpk[mi] = lds_read16(ring0 + rd_a + mi * 512);
+        if (!DUMP) sxs[mi] = lds_read8(ring0 + rd_sx + mi * 256);
+    }
 #pragma unroll
-        for (int j = 0; j < GS; ++j) {
-            const int g = s * GS + j;
-            if (g >= ng) break;
+    for (int ni = 0; ni < 2; ++ni) {
+        wpk[ni] = lds_read16(ring0 + rd_w + ni * 1024);
+        if (!DUMP) sfr[ni] = lds_read8(ring0 + rd_sf + ni * 512);
+    }
 
-            // every LDS operand of this group is requested up front (and the scheduler may not sink the
-            // reads next to their uses): LDS latency is then paid once per group, not once per MFMA
-            uint4 xpk[2], wpk[2], cn[2];
-            uint2 sxs[2], sfr[2];
-            uint32_t cp_[2];
+    int16v accP = magic;                       // tile (1,1) of the previous group, not yet folded into y
+    float16v SP = zero16;
+    uint4 cn[2], cm[2];                        // correction operands of the current pair of groups
+#pragma unroll
+    for (int i = 0; i < 2; ++i) cn[i] = cm[i] = uint4{0u, 0u, 0u, 0u};
+
+    auto fold = [&](const int16v& acc, const float16v& S, float16v& yy, const int g, const int ni, const int mi) {
+        if (DUMP) {
+            const int64_t m = m0 + wm * 64 + mi * 32 + l32;
+            if (g >= 0 && m >= dm0 && m < dm0 + dmt && m < M) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int n = n0 + wn * 64 + ni * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
+                    dacc[((m - dm0) * N + n) * ng + g] = (acc[i] - (int)MAGIC_BITS) >> 8;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) yy[i] = __builtin_fmaf(bits_f((uint32_t)acc[i]), S[i], yy[i]);
+        }
+    };
+    auto imma = [&](const int4v& wl, const int4v& wh, const int4v& xl, const int4v& xh) -> int16v {
+        int16v acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wl, xl, magic, 0, 0, 0);
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(wh, xh, acc, 0, 0, 0);
+    };
+    auto smma = [&](const uint2& sf, const uint2& sxv) -> float16v {
+        if (DUMP) return zero16;
+        return __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, sf), __builtin_bit_cast(short4v, sxv),
+                                                        zero16, 0, 0, 0);
+    };
+    // y -= 2.25 * (S_g + S_{g+1}) of one tile: issued right after the first of the two groups that add it, so y
+    // strays from the true partial sum by at most 2.25 * S in either direction
+    auto corr = [&](float16v& yy, const uint4& cnv, const uint4& cmv) {
+        if (!DUMP)
+            yy = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cnv), __builtin_bit_cast(bf16x8, cmv), yy, 0, 0, 0);
+    };
+
+    // One group (j = 0 or 1 of stage s, in slot `cur`).  FULL: stages s+1..s+3 and the next group exist, so every
+    // condition below is known at compile time and the body is straight-line code.
+    auto group_body = [&](const int s, const uint32_t cur, const uint32_t nxt, auto JC, auto FULLC) {
+        constexpr int j = decltype(JC)::value;
+        constexpr bool FULL = decltype(FULLC)::value;
+        const int g = 2 * s + j;
+        int4v xlo[2], xhi[2], wlo[2], whi[2];
+
+        // step 0: tile (0,0); finishes tile (1,1) of the previous group
+        unpack16(wpk[0], wlo[0], whi[0]);
+        unpack16(xpk[0], xlo[0], xhi[0]);
+        if (!DUMP && j == 0) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                cn[i] = lds_read16(cur + rd_cn + i * 1024);
+                const uint32_t cp = lds_read4(cur + rd_cp + i * 256);
+                cm[i] = uint4{cp, cp, cp, cp};
+            }
+        }
+        int16v acc0 = imma(wlo[0], whi[0], xlo[0], xhi[0]);
+        float16v S0 = smma(sfr[0], sxs[0]);
+        fold(accP, SP, y[1][1], g - 1, 1, 1);
+        if (j == 1) corr(y[1][1], cn[1], cm[1]);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // step 1: tile (0,1).  In the second group of a stage this wave no longer reads the current slot
+        // (everything was requested during the first group), so after the barrier the slot can take stage
+        // s+3; and stage s+1, requested two stages ago, is made visible for the prefetch in step 3.
+        unpack16(xpk[1], xlo[1], xhi[1]);
+        int16v acc1 = imma(wlo[0], whi[0], xlo[1], xhi[1]);
+        float16v S1 = smma(sfr[0], sxs[1]);
+        if (j == 1 && (FULL || s + 1 < nstages)) {
+            if (FULL || s + 2 < nstages) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (!DUMP) scale_store(s + 1, sc, FULL);
+            __syncthreads();
+            if (!DUMP && (FULL || s + 2 < nstages)) sc = scale_load(s + 2);
+            if (FULL || s + 3 < nstages) stage_issue(s + 3);
+        }
+        fold(acc0, S0, y[0][0], g, 0, 0);
+        if (j == 0) corr(y[0][0], cn[0], cm[0]);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // step 2: tile (1,0)
+        unpack16(wpk[1], wlo[1], whi[1]);
+        acc0 = imma(wlo[1], whi[1], xlo[0], xhi[0]);
+        S0 = smma(sfr[1], sxs[0]);
+        fold(acc1, S1, y[0][1], g, 0, 1);
+        if (j == 0) corr(y[0][1], cn[0], cm[1]);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // step 3: tile (1,1); then the operands of the next group into the registers its MFMAs have just read
+        accP = imma(wlo[1], whi[1], xlo[1], xhi[1]);
+        SP = smma(sfr[1], sxs[1]);
+        if (FULL || g + 1 < ng) {
+            const uint32_t src = (j == 0) ? cur : nxt;
+            constexpr uint32_t oa = (j == 0) ? 4096 : 0, osx = (j == 0) ? 1024 : 0, osf = (j == 0) ? 2048 : 0;
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi) {
-                const int rrow = wm * 64 + mi * 32 + l32;
-                xpk[mi] = cur.a[j][kh][rrow];
-                if (!DUMP) {
-                    const uint2* pe = kh ? &zero_entry : &cur.sxs[j][rrow];
-                    sxs[mi] = *pe;
-                    if (j == 0) cp_[mi] = cur.sxs[kh][rrow].x;     // lanes 0..31: group g, lanes 32..63: group g+1
-                }
+                xpk[mi] = lds_read16(src + rd_a + oa + mi * 512);
+                if (!DUMP) sxs[mi] = lds_read8(src + rd_sx + osx + mi * 256);
             }
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni) {
-                wpk[ni] = cur.w[j][wn * 2 + ni][lane];
-                if (!DUMP) {
-                    const uint2* pe = kh ? &zero_entry : &cur.sfr[j][wn * 2 + ni][l32];
-                    sfr[ni] = *pe;
-                    if (j == 0) cn[ni] = cur.cfr[wn * 2 + ni][lane];
-                }
+                wpk[ni] = lds_read16(src + rd_w + oa + ni * 1024);
+                if (!DUMP) sfr[ni] = lds_read8(src + rd_sf + osf + ni * 512);
             }
-            __builtin_amdgcn_sched_barrier(0);
-
-            // int4 -> 16*q bytes, in registers
-            int4v xlo[2], xhi[2];
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi) unpack16(xpk[mi], xlo[mi], xhi[mi]);
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                int4v wlo, whi;
-                unpack16(wpk[ni], wlo, whi);
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi) {
-                    int16v acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wlo, xlo[mi], magic, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(whi, xhi[mi], acc, 0, 0, 0);
-                    if (DUMP) {
-                        const int64_t m = m0 + wm * 64 + mi * 32 + l32;
-                        if (m >= dm0 && m < dm0 + dmt && m < M) {
-#pragma unroll
-                            for (int i = 0; i < 16; ++i) {
-                                const int n = n0 + wn * 64 + ni * 32 + 8 * (i >> 2) + 4 * kh + (i & 3);
-                                dacc[((m - dm0) * N + n) * ng + g] = (acc[i] - (int)MAGIC_BITS) >> 8;
-                            }
-                        }
-                    } else {
-                        const float16v S = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, sfr[ni]),
-                                                                                    __builtin_bit_cast(short4v, sxs[mi]), zero16, 0, 0, 0);
-#pragma unroll
-                        for (int i = 0; i < 16; ++i)
-                            y[ni][mi][i] = __builtin_fmaf(bits_f((uint32_t)acc[i]), S[i], y[ni][mi][i]);
-                    }
-                }
-            }
-            if (!DUMP && j == 0) {
-                // y -= 2.25 * (S_g + S_{g+1}) for the four tiles, between the two groups that add it: y then strays
-                // from the true partial sum by at most 2.25 * S in either direction
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi) {
-                    const uint4 cm = {cp_[mi], cp_[mi], cp_[mi], cp_[mi]};
-#pragma unroll
-                    for (int ni = 0; ni < 2; ++ni)
-                        y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cn[ni]),
-                                                                            __builtin_bit_cast(bf16x8, cm), y[ni][mi], 0, 0, 0);
-                }
-            }
-
         }
+        fold(acc0, S0, y[1][0], g, 1, 0);
+        if (j == 0) corr(y[1][0], cn[1], cm[0]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
-        if (more) {
-            wait_loads(more2 ? ndma : 0);
-            scale_store(nxt);
-        }
-        __syncthreads();
-        cur_i = nxt_i;
+    uint32_t cur = ring0;                      // slot of the stage being consumed
+    auto next_slot = [&](const uint32_t c) { return (c == ring0 + (NSLOTS - 1) * STAGE_BYTES) ? ring0 : c + STAGE_BYTES; };
+    int s = 0;
+    for (; s + 3 < nstages; ++s) {             // here 2 s + 7 < 2 nstages, so groups up to 2 s + 2 and stages up to s + 3 exist
+        const uint32_t nxt = next_slot(cur);
+        group_body(s, cur, nxt, IC<0>{}, IC<true>{});
+        group_body(s, cur, nxt, IC<1>{}, IC<true>{});
+        cur = nxt;
     }
+    for (; s < nstages; ++s) {
+        const uint32_t nxt = next_slot(cur);
+        group_body(s, cur, nxt, IC<0>{}, IC<false>{});
+        if (2 * s + 1 < ng) {
+            group_body(s, cur, nxt, IC<1>{}, IC<false>{});
+        } else {
+            corr(y[1][1], cn[1], cm[1]);       // odd group count: the last pair's correction for the tile still pending
+        }
+        cur = nxt;
+    }
+    fold(accP, SP, y[1][1], ng - 1, 1, 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may still be writing this block's LDS when it ends
 
     if (DUMP) return;
 
@@ -372,8 +449,8 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
 
 // Offline packing.  Region 1: weight fragments [N/32][K/64][64 lanes][16 B]: lane (n = lane % 32, kh = lane / 32)
 // holds bytes [32 g + 16 kh, +16) of row n of the canonical codes.  Region 2: n-side operands of the
-// scale-product MFMA, same indexing: lanes kh = 0 hold bf16 {w1, w1, w2, w2, 0, 0, 0, 0} with w1 + w2 ~ sw[g][n],
-// lanes kh = 1 zeros.  Region 3: n-side operands of the correction MFMA [N/32][ceil(ng/2)][64][16 B]: lane
+// scale-product MFMA [N/32][K/64][64 lanes][8 B]: lanes kh = 0 hold bf16 {w1, w1, w2, w2} with w1 + w2 ~ sw[g][n],
+// lanes kh = 1 zeros (the upper four k slots of that MFMA stay empty).  Region 3: n-side operands of the correction MFMA [N/32][ceil(ng/2)][64][16 B]: lane
 // (n, kh) holds, for group 2 gp + kh, bf16 {-2 w1, -2 w1, -2 w2, -2 w2, -w1/4, -w1/4, -w2/4, -w2/4}.
 __global__ void pack_weight_kernel(const uint8_t* __restrict__ qw, const float* __restrict__ sw,
                                    int N, int K, uint8_t* __restrict__ out) {
@@ -389,14 +466,18 @@ __global__ void pack_weight_kernel(const uint8_t* __restrict__ qw, const float* 
         o1[v] = *reinterpret_cast<const uint4*>(qw + (size_t)n * (K >> 1) + g * 32 + kh * 16);
     }
     uint2* o2 = reinterpret_cast<uint2*>(out + wfrag_bytes(N, K));
-    const size_t n2 = (size_t)(N >> 5) * ng * 32;
+    const size_t n2 = (size_t)(N >> 5) * ng * 64;
     for (size_t v = t0; v < n2; v += stride) {
-        const int l = (int)(v & 31);
-        const size_t fr = v >> 5;
+        const int l = (int)(v & 63);
+        const size_t fr = v >> 6;
         const int g = (int)(fr % ng), nb = (int)(fr / ng);
-        const uint32_t p = split_bf16(sw[(size_t)g * N + nb * 32 + l]);
-        const uint32_t w1 = p & 0xffffu, w2 = p >> 16;
-        o2[v] = uint2{w1 | (w1 << 16), w2 | (w2 << 16)};
+        uint2 e = {0u, 0u};
+        if (l < 32) {
+            const uint32_t p = split_bf16(sw[(size_t)g * N + nb * 32 + l]);
+            const uint32_t w1 = p & 0xffffu, w2 = p >> 16;
+            e = uint2{w1 | (w1 << 16), w2 | (w2 << 16)};
+        }
+        o2[v] = e;
     }
     uint4* o3 = reinterpret_cast<uint4*>(out + wfrag_bytes(N, K) + sfrag_bytes(N, K));
     const size_t n3 = (size_t)(N >> 5) * ngp * 64;
