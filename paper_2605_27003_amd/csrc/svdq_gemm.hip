@@ -86,6 +86,15 @@ __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sa), "s"(lds_off) : "memory");
 }
 
+// Same for one dword per lane: LDS byte offset lds_off + 4 l.
+__device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t lds_off) {
+    const uint64_t a = (uint64_t)(uintptr_t)sbase;
+    const uint64_t sa = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32)) << 32) |
+                        (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    lds_off = __builtin_amdgcn_readfirstlane(lds_off);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(sa), "s"(lds_off) : "memory");
+}
+
 // 4-bit codes -> 16*q bytes: even codes of each byte pair (k-step 0) and odd codes (k-step 1)
 __device__ __forceinline__ void unpack16(const uint4 v, int4v& lo, int4v& hi) {
     const uint32_t pk[4] = {v.x, v.y, v.z, v.w};
@@ -140,11 +149,12 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
     const int nbB = n0 >> 5;                                       // first 32-channel block of this tile
     const uint32_t ring0 = (uint32_t)(uintptr_t)(lds_byte*)ring;
 
-    // ---- staging.  Per stage (two groups) every wave issues six direct global->LDS loads of 1 KB: two of
-    // activation codes, two of weight fragments, one of correction operands, one of weight-scale pieces
-    // (NDMA = 4 without the scale data); the 256 token scales go through registers.  Global addresses are
-    // a wave-uniform base (advanced per stage on the scalar unit) plus a per-lane offset fixed for the kernel.
-    constexpr int NDMA = DUMP ? 4 : 6;
+    // ---- staging.  Per stage (two groups) every wave issues seven direct global->LDS loads: two of activation
+    // codes, two of weight fragments, one of correction operands, one of weight-scale pieces (1 KB each) and one
+    // of 64 raw token scales (NDMA = 4 without the scale data).  Nothing passes through registers, so the
+    // only waits are this code's own vmcnt waits and a whole stage can stay in flight behind the one awaited.
+    // Global addresses are a wave-uniform base plus a per-lane offset fixed for the kernel.
+    constexpr int NDMA = DUMP ? 4 : 7;
     uint32_t va[2], lds_a[2], lds_w[2];        // activation chunks c = 2 wave + i -> (group j = c/4, half sp = (c/2)%2, 64-row half rh = c%2)
     int cj[2];                                 // weight chunks      c = 2 wave + i -> (group j = c/4, n-block = c%4)
 #pragma unroll
@@ -160,9 +170,14 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
     const uint32_t vl16 = lane * 16;
     const uint32_t vsf = (uint32_t)(kh * ng * 512 + l32 * 16);       // scale pieces: lanes 0..31 one n-block, 32..63 the next
     const int sfj = wave >> 1, sfp = wave & 1;                        // this wave's (group, pair of n-blocks) of the scale pieces
-    const int xrow = tid & 127;                                       // token scales: waves 0,1 first group, waves 2,3 second
+    // token scales: wave w owns (group xg = w / 2, tokens 64 (w % 2) + lane).  The raw binary32 values land inside
+    // the LDS range that the same wave then overwrites with the expanded {p, p} entries (first quarter for the
+    // first half of the tokens, last quarter for the second half), so no other wave's data is touched.
+    const int xrow = tid & 127;
     const int xg = wave >> 1;
     const int64_t sxrow = (m0 + xrow < M) ? (m0 + xrow) : (M - 1);
+    const uint32_t vx = (uint32_t)(sxrow * 4);
+    const uint32_t raw_sx = OFF_SXS + xg * 1024 + (wave & 1) * 768;
 
     auto stage_issue = [&](const int s) {
         const uint32_t slot = ring0 + (uint32_t)(s % NSLOTS) * STAGE_BYTES;
@@ -175,16 +190,44 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
         if (!DUMP) {
             dma16(cfrag + ((size_t)(nbB + wave) * ngp + s) * 64, vl16, slot + OFF_CFR + wave * 1024);
             dma16(sfrag + ((size_t)(nbB + 2 * sfp) * ng + gj[sfj]) * 64, vsf, slot + OFF_SFR + (sfj * 4 + 2 * sfp) * 512);
+            dma4(sx + (size_t)gj[xg] * ldm, vx, slot + raw_sx);
         }
     };
-    // token scale of this thread's (group, token) of stage s, through a register
-    auto scale_load = [&](const int s) -> float {
-        const int gx = 2 * s + xg;
-        return sx[(size_t)(gx < ng ? gx : ng - 1) * ldm + sxrow];
-    };
-    auto scale_store = [&](const int s, const float sc, const bool exists = false) {
+    // raw token scale of this thread's (group, token), landed in `slot` -> {p, p} operand entry
+    const uint32_t wr_sx = OFF_SXS + (xg * BM + xrow) * 8;
+    auto scale_expand = [&](const int s, const uint32_t slot, const bool exists = false) {
+        const float sc = bits_f(lds_read4(slot + raw_sx + lane * 4));
         const uint32_t p = (exists || 2 * s + xg < ng) ? split_bf16(sc * SX_SCALE) : 0u;
-        lds_write8(ring0 + (uint32_t)(s % NSLOTS) * STAGE_BYTES + OFF_SXS + (xg * BM + xrow) * 8, uint2{p, p});
+        lds_write8(slot + wr_sx, uint2{p, p});
+    };
+
+    // The main loop streams: each of this wave's six transfers and its token-scale load keeps a wave-uniform
+    // pointer that advances by a constant per stage (two scalar adds), instead of being re-derived from s.
+    // Set to stage 3 / stage 2 here; the prologue and the last stages use the generic forms above.
+    const int cjw = wave >> 1;                                        // both chunks of a wave belong to the same group
+    const uint32_t vw[2] = {(uint32_t)((2 * (wave & 1) + 0) * ng * 1024) + vl16, (uint32_t)((2 * (wave & 1) + 1) * ng * 1024) + vl16};
+    const uint8_t* pa = qx + (size_t)(6 + cjw) * ldm * 32;
+    const uint4* pw = wfrag + ((size_t)nbB * ng + 6 + cjw) * 64;
+    const uint4* pc = DUMP ? nullptr : cfrag + ((size_t)(nbB + wave) * ngp + 3) * 64;
+    const uint2* ps = DUMP ? nullptr : sfrag + ((size_t)(nbB + 2 * sfp) * ng + 6 + sfj) * 64;
+    const float* px = DUMP ? nullptr : sx + (size_t)(6 + xg) * ldm;
+    const size_t step_a = (size_t)ldm * 64, step_x = (size_t)ldm * 2;
+    auto stream_issue = [&](const uint32_t slot) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            dma16(pa, va[i], slot + lds_a[i]);
+            dma16(pw, vw[i], slot + lds_w[i]);
+        }
+        pa += step_a;
+        pw += 128;
+        if (!DUMP) {
+            dma16(pc, vl16, slot + OFF_CFR + wave * 1024);
+            dma16(ps, vsf, slot + OFF_SFR + (sfj * 4 + 2 * sfp) * 512);
+            dma4(px, vx, slot + raw_sx);
+            pc += 64;
+            ps += 128;
+            px += step_x;
+        }
     };
 
     // per-lane LDS read offsets inside a slot
@@ -213,22 +256,14 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
     for (int i = 0; i < 16; ++i) zero16[i] = 0.0f;
 
     // prologue: stages 0..2 requested, stage 0 landed and visible, MFMA operands of group 0 requested
-    float sc = 0.0f;
-    {
-        float sc0 = 0.0f;
-        if (!DUMP) {
-            sc0 = scale_load(0);
-            if (nstages > 1) sc = scale_load(1);
-        }
-        stage_issue(0);
-        if (nstages > 1) stage_issue(1);
-        if (nstages > 2) stage_issue(2);
-        if (nstages > 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
-        else if (nstages > 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        if (!DUMP) scale_store(0, sc0);
-        __syncthreads();
-    }
+    stage_issue(0);
+    if (nstages > 1) stage_issue(1);
+    if (nstages > 2) stage_issue(2);
+    if (nstages > 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
+    else if (nstages > 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (!DUMP) scale_expand(0, ring0);
+    __syncthreads();
     // ---- main loop.  One step = one 32 x 32 tile of one group: its two integer MFMAs and its scale-product
     // MFMA are issued, and while they run the vector ALU finishes the PREVIOUS tile (16 FMAs on results that
     // completed a step ago) and unpacks operands.  All LDS operands are requested one group ahead.
@@ -316,10 +351,10 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
         if (j == 1 && (FULL || s + 1 < nstages)) {
             if (FULL || s + 2 < nstages) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            if (!DUMP) scale_store(s + 1, sc, FULL);
+            if (!DUMP) scale_expand(s + 1, nxt, FULL);
             __syncthreads();
-            if (!DUMP && (FULL || s + 2 < nstages)) sc = scale_load(s + 2);
-            if (FULL || s + 3 < nstages) stage_issue(s + 3);
+            if (FULL) stream_issue(cur);
+            else if (s + 3 < nstages) stage_issue(s + 3);
         }
         fold(acc0, S0, y[0][0], g, 0, 0);
         if (j == 0) corr(y[0][0], cn[0], cm[0]);
@@ -358,7 +393,8 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
     uint32_t cur = ring0;                      // slot of the stage being consumed
     auto next_slot = [&](const uint32_t c) { return (c == ring0 + (NSLOTS - 1) * STAGE_BYTES) ? ring0 : c + STAGE_BYTES; };
     int s = 0;
-    for (; s + 3 < nstages; ++s) {             // here 2 s + 7 < 2 nstages, so groups up to 2 s + 2 and stages up to s + 3 exist
+    const int nfull = ng >> 1;                 // stages with both groups
+    for (; s + 3 < nfull; ++s) {               // stages up to s + 3 are complete: no clamping, no conditions
         const uint32_t nxt = next_slot(cur);
         group_body(s, cur, nxt, IC<0>{}, IC<true>{});
         group_body(s, cur, nxt, IC<1>{}, IC<true>{});
