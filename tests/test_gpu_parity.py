@@ -111,6 +111,28 @@ def test_strided_input_and_output(svdq, oracle):
     assert torch.all(ybuf[:, N:] == 7.0)                       # padding untouched
 
 
+def test_fused_qkv_equals_three_projections(svdq, oracle):
+    """Three projections that share an input (q, k, v) as ONE N = 3n GEMM after ONE quantise pass: the fused
+    output must equal, bit for bit, the three column-sliced GEMMs written into a strided output, and match
+    the oracle like any other layer."""
+    M, K, n, r = 200, 512, 256, 32
+    x, L = small_layer(21, M, K, 3 * n, r)
+    DL = DeviceLayer(L)
+    qx, sx, h = run_quant(svdq, x, DL, 0.8)
+    oq, os_, oh = check_quant(oracle, x, L, 0.8, qx, sx, h, "qkv")
+    y = svdq.linear_w4a4(qx, sx, DL.wp, 3 * n, h, DL.L2, DL.bias)
+    y32 = svdq.linear_w4a4(qx, sx, DL.wp, 3 * n, h, DL.L2, DL.bias, out_dtype=torch.float32)
+    parts = torch.full((M, 3 * n), 7.0, dtype=torch.bfloat16, device="cuda")
+    for i in range(3):
+        sl = slice(i * n, (i + 1) * n)
+        wp = svdq.pack_weight(DL.qw[sl].contiguous(), DL.sw[:, sl].contiguous())
+        svdq.linear_w4a4(qx, sx, wp, n, h, DL.L2[:, sl].contiguous(), DL.bias[sl].contiguous(), out=parts[:, sl])
+    torch.cuda.synchronize()
+    assert torch.equal(parts, y)
+    orc = oracle.linear(oq, os_, L.qw, L.sw, oh, L.L2, L.bias)
+    check_y(host_bits(y), y32.cpu().numpy(), orc, "qkv")
+
+
 def test_degenerate_groups_and_ties(svdq, oracle):
     """All-zero rows and groups, a denormal group, the hand-worked tie vectors, codes at both range ends."""
     K = 256
