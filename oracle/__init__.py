@@ -160,3 +160,62 @@ def linear(qx, sx, qw, sw, h=None, L2_bf16=None, bias=None, want=("y64", "y32", 
         _p(out.get("ybf16"), ctypes.c_uint16), ctypes.c_int(nthreads))
     _chk(rc, "linear")
     return out
+
+
+# ---- MXFP4 variant -----------------------------------------------------------
+def e2m1_value(code):
+    f = lib().svdq_oracle_e2m1_value
+    f.restype = ctypes.c_float
+    return float(f(ctypes.c_int(int(code))))
+
+
+def quantize_act_mxfp4(x_bf16, inv_lambda, rho, nthreads=0):
+    """x_bf16 [M,K] uint16 -> (qx [M,K/2] u8 packed E2M1 codes, sx [M,K/32] u8 E8M0 scale bytes)."""
+    assert x_bf16.dtype == np.uint16 and x_bf16.ndim == 2 and x_bf16.strides[1] == 2
+    M, K = x_bf16.shape
+    ldx = x_bf16.strides[0] // 2 if M > 1 else K
+    il = _c(inv_lambda, np.float32)
+    qx = np.empty((M, K // 2), np.uint8)
+    sx = np.empty((M, K // 32), np.uint8)
+    rc = lib().svdq_oracle_quantize_act_mxfp4(
+        _p(x_bf16, ctypes.c_uint16), ctypes.c_int64(ldx), _p(il, ctypes.c_float),
+        ctypes.c_float(rho), ctypes.c_int64(M), ctypes.c_int(K),
+        _p(qx, ctypes.c_uint8), _p(sx, ctypes.c_uint8), ctypes.c_int(nthreads))
+    _chk(rc, "quantize_act_mxfp4")
+    return qx, sx
+
+
+def linear_mxfp4(qx, sx, qw, sw, h=None, L2_bf16=None, bias=None, want=("y64", "y32", "ybf16"), nthreads=0):
+    """MXFP4 layer from quantised activations -> dict of requested outputs.  sx [M,K/32] u8, sw [K/32,N] u8."""
+    qx = _c(qx, np.uint8)
+    sx = _c(sx, np.uint8)
+    qw = _c(qw, np.uint8)
+    sw = _c(sw, np.uint8)
+    M, K2 = qx.shape
+    K = 2 * K2
+    N = qw.shape[0]
+    assert qw.shape == (N, K2) and sx.shape == (M, K // 32) and sw.shape == (K // 32, N)
+    r = 0
+    if h is not None:
+        h = _c(h, np.float64)
+        L2_bf16 = _c(L2_bf16, np.uint16)
+        r = h.shape[1]
+        assert h.shape == (M, r) and L2_bf16.shape == (r, N)
+    if bias is not None:
+        bias = _c(bias, np.float32)
+        assert bias.shape == (N,)
+    out = {}
+    if "y64" in want:
+        out["y64"] = np.empty((M, N), np.float64)
+    if "y32" in want:
+        out["y32"] = np.empty((M, N), np.float32)
+    if "ybf16" in want:
+        out["ybf16"] = np.empty((M, N), np.uint16)
+    rc = lib().svdq_oracle_linear_mxfp4(
+        _p(qx, ctypes.c_uint8), _p(sx, ctypes.c_uint8), _p(qw, ctypes.c_uint8), _p(sw, ctypes.c_uint8),
+        _p(h, ctypes.c_double), _p(L2_bf16, ctypes.c_uint16), _p(bias, ctypes.c_float),
+        ctypes.c_int64(M), ctypes.c_int(N), ctypes.c_int(K), ctypes.c_int(r),
+        _p(out.get("y64"), ctypes.c_double), _p(out.get("y32"), ctypes.c_float),
+        _p(out.get("ybf16"), ctypes.c_uint16), ctypes.c_int(nthreads))
+    _chk(rc, "linear_mxfp4")
+    return out

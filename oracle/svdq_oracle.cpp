@@ -196,4 +196,112 @@ float svdq_oracle_alpha_lookup(const float* table, int nbins, int step, int step
     return table[bin];
 }
 
+/* ---- MXFP4 variant ---------------------------------------------------- */
+
+static const float kE2M1[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+
+float svdq_oracle_e2m1_value(int code) {
+    float v = kE2M1[code & 7];
+    return (code & 8) ? -v : v;
+}
+
+/* Magnitude code (0..7) of the E2M1 value nearest to mag >= 0: ties go to the
+ * even code, anything beyond the largest magnitude saturates to it. */
+static int e2m1_nearest(float mag) {
+    int best = 0;
+    float bestd = mag;                                /* distance to code 0 */
+    for (int c = 1; c < 8; ++c) {
+        float d = std::fabs(mag - kE2M1[c]);
+        if (d < bestd || (d == bestd && (c & 1) == 0)) { best = c; bestd = d; }
+    }
+    return best;
+}
+
+int svdq_oracle_quantize_act_mxfp4(const uint16_t* x, int64_t ldx, const float* inv_lambda,
+                                   float rho, int64_t M, int K,
+                                   uint8_t* qx, uint8_t* sx, int nthreads) {
+    const int B = SVDQ_ORACLE_MX_BLOCK;
+    if (!x || !inv_lambda || !qx || !sx || M < 0 || K <= 0 || K % B || ldx < K) return -1;
+    if (!(rho > 0.0f) || !(rho <= 1.0f)) return -1;
+    const int nb = K / B;
+    for_rows(M, nthreads, [=](int64_t m0, int64_t m1) {
+        float xs[SVDQ_ORACLE_MX_BLOCK];
+        int   q[SVDQ_ORACLE_MX_BLOCK];
+        for (int64_t m = m0; m < m1; ++m) {
+            for (int b = 0; b < nb; ++b) {
+                float a = 0.0f;
+                for (int i = 0; i < B; ++i) {
+                    int k = b * B + i;
+                    xs[i] = svdq_oracle_bf16_to_f32(x[m * ldx + k]) * inv_lambda[k];   /* eq. 5 */
+                    float ax = std::fabs(xs[i]);
+                    if (ax > a) a = ax;
+                }
+                float alpha = rho * a;                                                /* eq. 8 */
+                int e8 = 0;
+                if (alpha >= 4.70197740e-38f) {                                       /* 2^-124 */
+                    int E;                                                            /* alpha = f * 2^E, f in [0.5,1) */
+                    (void)std::frexp(alpha, &E);
+                    int shared = (E - 1) - 2;                                         /* floor(log2 alpha) - 2 */
+                    e8 = shared + 127;
+                    float X = std::ldexp(1.0f, shared);
+                    for (int i = 0; i < B; ++i) {
+                        float v = xs[i] / X;                                          /* exact: power of two */
+                        int code = e2m1_nearest(std::fabs(v));
+                        if (std::signbit(xs[i])) code |= 8;
+                        q[i] = code;
+                    }
+                } else {
+                    for (int i = 0; i < B; ++i) q[i] = 0;
+                }
+                sx[m * nb + b] = (uint8_t)e8;
+                for (int i = 0; i < B; i += 2) {
+                    int k = b * B + i;
+                    qx[m * (K / 2) + k / 2] = (uint8_t)(q[i] | (q[i + 1] << 4));
+                }
+            }
+        }
+    });
+    return 0;
+}
+
+int svdq_oracle_linear_mxfp4(const uint8_t* qx, const uint8_t* sx,
+                             const uint8_t* qw, const uint8_t* sw,
+                             const double* h, const uint16_t* L2, const float* bias,
+                             int64_t M, int N, int K, int r,
+                             double* y64, float* y32, uint16_t* ybf16, int nthreads) {
+    const int B = SVDQ_ORACLE_MX_BLOCK;
+    if (!qx || !sx || !qw || !sw || M < 0 || N <= 0 || K <= 0 || K % B || r < 0) return -1;
+    if (r > 0 && (!h || !L2)) return -1;
+    const int nb = K / B;
+    for_rows(M, nthreads, [=](int64_t m0, int64_t m1) {
+        std::vector<float> arow(K);
+        for (int64_t m = m0; m < m1; ++m) {
+            for (int k = 0; k < K; ++k) {
+                int nib = (k & 1) ? (qx[m * (K / 2) + k / 2] >> 4) : (qx[m * (K / 2) + k / 2] & 0xF);
+                arow[k] = svdq_oracle_e2m1_value(nib);
+            }
+            for (int n = 0; n < N; ++n) {
+                const uint8_t* wrow = qw + (int64_t)n * (K / 2);
+                double y = 0.0;
+                for (int b = 0; b < nb; ++b) {
+                    double dot = 0.0;                                    /* exact: multiples of 1/4, small */
+                    for (int k = b * B; k < (b + 1) * B; ++k) {
+                        int nib = (k & 1) ? (wrow[k / 2] >> 4) : (wrow[k / 2] & 0xF);
+                        dot += (double)arow[k] * (double)svdq_oracle_e2m1_value(nib);
+                    }
+                    y += dot * std::ldexp(1.0, (int)sx[m * nb + b] - 127) * std::ldexp(1.0, (int)sw[(int64_t)b * N + n] - 127);
+                }
+                for (int j = 0; j < r; ++j)
+                    y += h[m * r + j] * (double)svdq_oracle_bf16_to_f32(L2[(int64_t)j * N + n]);
+                if (bias) y += (double)bias[n];
+                float yf = (float)y;
+                if (y64) y64[m * N + n] = y;
+                if (y32) y32[m * N + n] = yf;
+                if (ybf16) ybf16[m * N + n] = svdq_oracle_f32_to_bf16(yf);
+            }
+        }
+    });
+    return 0;
+}
+
 }  /* extern "C" */

@@ -103,6 +103,47 @@ int svdq_oracle_linear(const uint8_t* qx, const float* sx,
  */
 float svdq_oracle_alpha_lookup(const float* table, int nbins, int step, int step0, int nsteps_expert);
 
+/* ------------------------------------------------------------------------
+ * MXFP4 variant: the 4-bit data format the paper's tables are quoted in
+ * (caption of Table I).  Same layer (eq. 5, 7, 8, 11); the uniform integer
+ * grid of eq. 3 is replaced by the microscaling FP4 format: blocks of 32
+ * values along K share one power-of-two scale (E8M0 byte e, value 2^(e-127)),
+ * elements are E2M1 (sign, 2 exponent bits, 1 mantissa bit: magnitudes
+ * 0, 0.5, 1, 1.5, 2, 3, 4, 6).  Conversion follows the published MX rule with
+ * the clipped threshold of eq. 8 as the block's reference magnitude:
+ *
+ *   x^     = x * inv_lambda                          (eq. 5, binary32)
+ *   a      = max_{k in block} |x^|
+ *   alpha  = rho * a                                 (eq. 8, binary32)
+ *   E      = floor(log2(alpha));  X = 2^(E - 2)      (2 = exponent of the
+ *                                                     largest E2M1 binade)
+ *   code   = E2M1 nearest to x^ / X, ties to the even code, |.| > 6 -> 6
+ *   sign bit of the code = sign bit of x^
+ *
+ * A block with alpha < 2^-124 (in particular an all-zero block) is empty:
+ * scale byte 0 and all codes 0.  Packed codes: byte j of a row holds code 2j
+ * in its low nibble, code 2j+1 in its high nibble.
+ */
+enum { SVDQ_ORACLE_MX_BLOCK = 32 };
+
+/* Value of a 4-bit E2M1 code (bit 3 = sign). */
+float svdq_oracle_e2m1_value(int code);
+
+/*   qx out [M, K/2] packed E2M1 codes;  sx out [M, K/32] E8M0 bytes.  K % 32 == 0. */
+int svdq_oracle_quantize_act_mxfp4(const uint16_t* x, int64_t ldx, const float* inv_lambda,
+                                   float rho, int64_t M, int K,
+                                   uint8_t* qx, uint8_t* sx, int nthreads);
+
+/*
+ * y = sum_blocks (sum_{k in block} vx[m,k] vw[n,k]) 2^(sx[m,b]-127) 2^(sw[b,n]-127) + h L2 + bias
+ *   qw [N, K/2] packed E2M1 codes, sw [K/32, N] E8M0 bytes; the rest as svdq_oracle_linear.
+ */
+int svdq_oracle_linear_mxfp4(const uint8_t* qx, const uint8_t* sx,
+                             const uint8_t* qw, const uint8_t* sw,
+                             const double* h, const uint16_t* L2, const float* bias,
+                             int64_t M, int N, int K, int r,
+                             double* y64, float* y32, uint16_t* ybf16, int nthreads);
+
 #ifdef __cplusplus
 }
 #endif

@@ -128,6 +128,45 @@ def rtn_int4_weight(R: np.ndarray):
     return qw, sw
 
 
+MX_BLOCK = 32
+E2M1_VALUES = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], np.float32)
+
+
+def mxfp4_weight(R: np.ndarray):
+    """R [K,N] float32 -> (qw [N,K/2] packed E2M1 codes, sw [K/32,N] uint8 E8M0 scale bytes).
+
+    Microscaling FP4 per output channel, per 32-block along K: shared exponent
+    floor(log2(absmax)) - 2, element = nearest E2M1 value of R / 2^shared (ties
+    to the even code, saturating at 6); an all-zero block gets byte 0, codes 0.
+    """
+    K, N = R.shape
+    nb = K // MX_BLOCK
+    Rb = R.reshape(nb, MX_BLOCK, N).astype(np.float32)
+    amax = np.abs(Rb).max(axis=1)                                              # [nb,N]
+    live = amax >= np.float32(2.0 ** -124)
+    _, E = np.frexp(np.where(live, amax, np.float32(1.0)))                     # amax = f * 2^E, f in [0.5,1)
+    shared = (E - 1) - 2
+    X = np.ldexp(np.float32(1.0), shared).astype(np.float32)
+    v = np.abs(Rb) / X[:, None, :]
+    code = ((v > 0.25).astype(np.uint8) + (v >= 0.75) + (v > 1.25) + (v >= 1.75) + (v > 2.5) + (v >= 3.5)
+            + (v > 5.0)).astype(np.uint8)
+    code |= (np.signbit(Rb).astype(np.uint8) << 3)
+    code = np.where(live[:, None, :], code, 0).astype(np.uint8)
+    sw = np.where(live, shared + 127, 0).astype(np.uint8)
+    cT = np.ascontiguousarray(code.reshape(K, N).T)                             # [N,K]
+    qw = (cT[:, 0::2] | (cT[:, 1::2] << 4)).astype(np.uint8)
+    return qw, sw
+
+
+def unpack_e2m1(q: np.ndarray) -> np.ndarray:
+    """[R,K/2] packed E2M1 codes -> [R,K] float32 values."""
+    out = np.empty((q.shape[0], q.shape[1] * 2), np.uint8)
+    out[:, 0::2] = q & 0xF
+    out[:, 1::2] = q >> 4
+    v = E2M1_VALUES[out & 7]
+    return np.where(out & 8, -v, v).astype(np.float32)
+
+
 def unpack_int4(q: np.ndarray) -> np.ndarray:
     """[R,K/2] packed -> [R,K] int8 signed codes."""
     lo = (q & 0xF).astype(np.int8)
@@ -150,15 +189,16 @@ class Layer:
     inv_lambda: np.ndarray     # [K] f32, RN(1/lam)
     L1: np.ndarray             # [K,r] bf16 bits
     L2: np.ndarray             # [r,N] bf16 bits
-    qw: np.ndarray             # [N,K/2] packed int4 codes of the residual
-    sw: np.ndarray             # [K/64,N] f32 scales
+    qw: np.ndarray             # [N,K/2] packed 4-bit codes of the residual (int4, or E2M1 for fmt "mxfp4")
+    sw: np.ndarray             # int4: [K/64,N] f32 scales; mxfp4: [K/32,N] uint8 E8M0 bytes
     bias: np.ndarray           # [N] f32
     W: Optional[np.ndarray] = None   # dense [K,N] f32, only kept on request
+    fmt: str = "int4"
 
 
 def make_layer(seed: int, K: int, N: int, r: int, x_colmax: np.ndarray,
                w_outlier_cols: int = 0, w_outlier_scale: float = 1.0,
-               keep_dense: bool = False) -> Layer:
+               keep_dense: bool = False, fmt: str = "int4") -> Layer:
     g = _rng(seed, 3)
     W = g.standard_normal((K, N), dtype=np.float32) * np.float32(0.02)
     if w_outlier_cols:
@@ -177,9 +217,9 @@ def make_layer(seed: int, K: int, N: int, r: int, x_colmax: np.ndarray,
         L1 = np.zeros((K, 0), np.uint16)
         L2 = np.zeros((0, N), np.uint16)
         R = What
-    qw, sw = rtn_int4_weight(R.astype(np.float32))
+    qw, sw = (mxfp4_weight if fmt == "mxfp4" else rtn_int4_weight)(R.astype(np.float32))
     bias = (_rng(seed, 5).standard_normal(N, dtype=np.float32) * np.float32(0.01)).astype(np.float32)
-    return Layer(K, N, r, lam, inv_lambda, L1, L2, qw, sw, bias, W if keep_dense else None)
+    return Layer(K, N, r, lam, inv_lambda, L1, L2, qw, sw, bias, W if keep_dense else None, fmt)
 
 
 # --------------------------------------------------------------------------
@@ -203,7 +243,7 @@ def _table(seed, nbins, probs=None):
     return [float(v) for v in g.choice(RATIOS, size=nbins, p=probs)]
 
 
-def workload(idx: int, M: Optional[int] = None, keep_dense: bool = False) -> Workload:
+def workload(idx: int, M: Optional[int] = None, keep_dense: bool = False, fmt: str = "int4") -> Workload:
     """Workload `idx` (0-based; the five configurations of the benchmark definition).
 
     `M` overrides the token count (tests use it for row-reduced variants that
@@ -212,22 +252,22 @@ def workload(idx: int, M: Optional[int] = None, keep_dense: bool = False) -> Wor
     if idx == 0:
         M = M or 256
         x, cm = make_x(0, M, 512, outlier_count=4, outlier_scale=40.0)
-        L = make_layer(0, 512, 512, 16, cm, w_outlier_cols=4, w_outlier_scale=10.0, keep_dense=keep_dense)
+        L = make_layer(0, 512, 512, 16, cm, w_outlier_cols=4, w_outlier_scale=10.0, keep_dense=keep_dense, fmt=fmt)
         return Workload("c1_tiny", M, {"x": x}, {"e0/lin": L}, {"lin": "x"}, {"e0": [0.9]})
     if idx == 1:
         M = M or 32760
         x, cm = make_x(2, M, 5120, outlier_frac=0.005, outlier_scale=50.0)
-        L = make_layer(2, 5120, 5120, 32, cm, keep_dense=keep_dense)
+        L = make_layer(2, 5120, 5120, 32, cm, keep_dense=keep_dense, fmt=fmt)
         return Workload("c2_attn_o", M, {"x": x}, {"e0/lin": L}, {"lin": "x"}, {"e0": _table(2, 4)})
     if idx == 2:
         M = M or 32760
         x, cm = make_x(3, M, 5120, outlier_frac=0.005, outlier_scale=50.0, heavy_count=8, heavy_scale=100.0)
-        L = make_layer(3, 5120, 13824, 32, cm, keep_dense=keep_dense)
+        L = make_layer(3, 5120, 13824, 32, cm, keep_dense=keep_dense, fmt=fmt)
         return Workload("c3_ffn_up", M, {"x": x}, {"e0/lin": L}, {"lin": "x"}, {"e0": [0.9, 0.8, 0.8, 0.9]})
     if idx == 3:
         M = M or 32760
         x, cm = make_x(4, M, 13824, kind="gelu", sigma=1.5)
-        L = make_layer(4, 13824, 5120, 32, cm, keep_dense=keep_dense)
+        L = make_layer(4, 13824, 5120, 32, cm, keep_dense=keep_dense, fmt=fmt)
         return Workload("c4_ffn_down", M, {"x": x}, {"e0/lin": L}, {"lin": "x"}, {"e0": [0.8, 0.8, 0.7, 0.8]})
     if idx == 4:
         M = M or 75600
@@ -245,7 +285,7 @@ def workload(idx: int, M: Optional[int] = None, keep_dense: bool = False) -> Wor
                 jobs.append((f"{ename}/{lin}", 500 + 10 * e + j, K, N, cms[inp]))
             tables[ename] = _table(540 + e, 8, probs=[0.05, 0.1, 0.55, 0.25, 0.05])
         with ThreadPoolExecutor(max_workers=4) as ex:
-            made = ex.map(lambda j: make_layer(j[1], j[2], j[3], 32, j[4], keep_dense=keep_dense), jobs)
+            made = ex.map(lambda j: make_layer(j[1], j[2], j[3], 32, j[4], keep_dense=keep_dense, fmt=fmt), jobs)
             for job, L in zip(jobs, made):
                 layers[job[0]] = L
         return Workload("c5_block_720p", M, xs, layers, {k: v[0] for k, v in shapes.items()}, tables,
