@@ -156,6 +156,35 @@ int svdq_debug_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int
                          int64_t m0, int mt, int32_t* acc, void* stream);
 
 /*
+ * ---- MXFP4 variant: the 4-bit data format of the paper's Table I on the block-scaled
+ * matrix instruction of gfx950.  Same layer (eq. 5, 7, 8, 11) and same calling conventions;
+ * the integer grid of eq. 3 is replaced by microscaling FP4: blocks of 32 values along K share
+ * one E8M0 scale byte e (value 2^(e-127)), elements are E2M1 codes (bit 3 sign, magnitudes
+ * 0, 0.5, 1, 1.5, 2, 3, 4, 6).  Conversion: a = max|x^| over the block, alpha = rho * a (eq. 8),
+ * shared exponent floor(log2 alpha) - 2, element = E2M1 nearest to x^ / 2^shared (ties to the even
+ * code, saturating at 6, sign bit of x^); a block with alpha < 2^-124 gets byte 0 and codes 0.
+ *
+ *   qx   [K/64][M][32 B]: packed E2M1 codes, same container as the int4 path (the 32 bytes of a
+ *        token and 64-group are two MX blocks: bytes 0..15 and 16..31)
+ *   sx   [ceil(K/128)][M][2][2] bytes: for token m and pair of 64-groups (2s, 2s+1) the byte
+ *        [h][j] scales MX block 2 (2s + j) + h, i.e. k in [64 (2s + j) + 32 h, +32); bytes of a
+ *        group past K are 0
+ *   weights at the boundary: qw [N, K/2] packed E2M1 codes, sw [K/32, N] E8M0 bytes
+ * The matrix core applies the block scales and accumulates in binary32 over all of K; there is
+ * no integer accumulator and no per-group step.  Codes and scale bytes are bit-exact against the
+ * definition; y is compared within the layer's tolerance.
+ */
+int svdq_quantize_act_mxfp4(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                            const void* l1_packed, int64_t M, int K, int r,
+                            uint8_t* qx, uint8_t* sx_e8m0, float* h, void* stream);
+size_t svdq_packed_weight_mxfp4_bytes(int N, int K);
+int svdq_pack_weight_mxfp4(const uint8_t* qw, const uint8_t* sw_e8m0, int N, int K, void* w_packed, void* stream);
+int svdq_linear_mxfp4(const uint8_t* qx, const uint8_t* sx_e8m0, const void* w_packed,
+                      const float* h, const void* L2_bf16, const float* bias,
+                      int64_t M, int N, int K, int r,
+                      void* y, int64_t ldy, int out_dtype, void* stream);
+
+/*
  * Test hook: the scalar part of kernel (a)'s chain, eq. 8-9, evaluated by the
  * kernel's own device functions on n given group magnitudes a[i] >= 0:
  *   s[i]   = (rho * a[i]) / 7, or 0 when that is not a normal number

@@ -10,5 +10,6 @@ from .binding import (  # noqa: F401
     SvdqError, alpha_lookup, debug_group_acc, debug_scale_chain, linear_w4a4, load_library, lowrank,
     pack_lowrank_down, pack_weight, packed_l1_bytes, packed_weight_bytes, quantize_act, version,
     to_group_major, to_token_major,
+    quantize_act_mxfp4, mx_to_token_major, packed_weight_mxfp4_bytes, pack_weight_mxfp4, linear_mxfp4,
     W4A4Linear,
 )

@@ -22,6 +22,10 @@ EXPORTS = {
     "svdq_pack_weight": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
     "svdq_linear_w4a4": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _i32, _vp]),
     "svdq_lowrank": (_i32, [_i32, _vp, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _i64, _vp]),
+    "svdq_quantize_act_mxfp4": (_i32, [_vp, _i64, _vp, _f32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "svdq_packed_weight_mxfp4_bytes": (ctypes.c_size_t, [_i32, _i32]),
+    "svdq_pack_weight_mxfp4": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
+    "svdq_linear_mxfp4": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _i32, _vp]),
     "svdq_debug_group_acc": (_i32, [_vp, _vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp]),
     "svdq_debug_scale_chain": (_i32, [_vp, _f32, _i64, _vp, _vp, _vp]),
 }
@@ -172,6 +176,59 @@ def debug_group_acc(qx, w_packed, N, m0, mt):
     _check(load_library().svdq_debug_group_acc(_ptr(qx), _ptr(w_packed), M, N, K, m0, mt, _ptr(acc), _stream()),
            "svdq_debug_group_acc")
     return acc
+
+
+# ---- MXFP4 variant ---------------------------------------------------------------------------
+def quantize_act_mxfp4(x_bf16, inv_lambda, rho, l1_packed=None, r=0, out=None):
+    """x [M,K] bf16 -> (qx [K/64,M,32] u8 E2M1 codes, sx [ceil(K/128),M,2,2] u8 E8M0 bytes, h [M,r] f32 or None)."""
+    M, K = x_bf16.shape
+    ldx = x_bf16.stride(0) if M > 1 else K
+    if out is None:
+        qx = torch.empty((K // 64, M, 32), dtype=torch.uint8, device=x_bf16.device)
+        sx = torch.empty(((K // 64 + 1) // 2, M, 2, 2), dtype=torch.uint8, device=x_bf16.device)
+        h = torch.empty((M, r), dtype=torch.float32, device=x_bf16.device) if l1_packed is not None else None
+    else:
+        qx, sx, h = out
+    _check(load_library().svdq_quantize_act_mxfp4(_ptr(x_bf16), ldx, _ptr(inv_lambda), float(rho), _ptr(l1_packed),
+                                                  M, K, r if l1_packed is not None else 0,
+                                                  _ptr(qx), _ptr(sx), _ptr(h), _stream()), "svdq_quantize_act_mxfp4")
+    return qx, sx, h
+
+
+def mx_to_token_major(qx, sx, K):
+    """Group-major MXFP4 activations -> (qx [M,K/2], sx [M,K/32]): the layout the format's definition suggests."""
+    ng, M, _ = qx.shape
+    qx_tm = qx.permute(1, 0, 2).reshape(M, ng * 32).contiguous()
+    # sx[s][m][h][j] scales MX block 2 (2s + j) + h  ->  [m][s][j][h]
+    sx_tm = sx.permute(1, 0, 3, 2).reshape(M, -1)[:, : K // 32].contiguous()
+    return qx_tm, sx_tm
+
+
+def packed_weight_mxfp4_bytes(N, K):
+    return int(load_library().svdq_packed_weight_mxfp4_bytes(N, K))
+
+
+def pack_weight_mxfp4(qw, sw):
+    """qw [N,K/2] u8 packed E2M1 codes, sw [K/32,N] u8 E8M0 bytes (device) -> opaque uint8 tensor for linear_mxfp4."""
+    N, K2 = qw.shape
+    K = 2 * K2
+    out = torch.empty(packed_weight_mxfp4_bytes(N, K), dtype=torch.uint8, device=qw.device)
+    _check(load_library().svdq_pack_weight_mxfp4(_ptr(qw), _ptr(sw), N, K, _ptr(out), _stream()), "svdq_pack_weight_mxfp4")
+    return out
+
+
+def linear_mxfp4(qx, sx, w_packed, N, h=None, L2_bf16=None, bias=None, out=None, out_dtype=torch.bfloat16):
+    """MXFP4 layer from quantised activations -> y [M,N] bf16 (or f32: the value before the bf16 rounding)."""
+    ng, M, _ = qx.shape
+    K = 64 * ng
+    r = 0 if h is None else h.shape[1]
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=qx.device)
+    code = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
+    ldy = out.stride(0) if M > 1 else N
+    _check(load_library().svdq_linear_mxfp4(_ptr(qx), _ptr(sx), _ptr(w_packed), _ptr(h), _ptr(L2_bf16), _ptr(bias),
+                                            M, N, K, r, _ptr(out), ldy, code, _stream()), "svdq_linear_mxfp4")
+    return out
 
 
 def debug_scale_chain(a, rho):

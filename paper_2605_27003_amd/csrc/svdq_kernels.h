@@ -24,6 +24,17 @@ hipError_t launch_linear(const uint8_t* qx, const float* sx, const void* w_packe
 hipError_t launch_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int N, int K,
                             int64_t m0, int mt, int32_t* acc, hipStream_t stream);
 
+// svdq_mxfp4.hip
+size_t packed_weight_mx_bytes(int N, int K);
+hipError_t launch_pack_weight_mx(const uint8_t* qw, const uint8_t* sw, int N, int K, void* out, hipStream_t stream);
+hipError_t launch_quantize_mx(const void* x, int64_t ldx, const float* inv_lambda, float rho,
+                              const void* l1p, int64_t M, int K, int r,
+                              uint8_t* qx, uint8_t* sxe, float* h, hipStream_t stream);
+hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w_packed,
+                            const float* h, const void* L2, const float* bias,
+                            int64_t M, int N, int K, int r, void* y, int64_t ldy, int out_f32,
+                            hipStream_t stream);
+
 // svdq_lowrank.hip
 hipError_t launch_lowrank_down(const void* x, int64_t ldx, const float* inv_lambda, const void* L1,
                                int64_t M, int K, int r, float* h, hipStream_t stream);

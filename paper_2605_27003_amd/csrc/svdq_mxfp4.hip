@@ -1,0 +1,531 @@
+// MXFP4 variant of the layer: the 4-bit format of the paper's Table I (E2M1 elements, one E8M0
+// power-of-two scale per 32 values along K) on the block-scaled matrix instruction of gfx950,
+// v_mfma_scale_f32_32x32x64_f8f6f4.  The matrix core applies both operands' block scales itself and
+// accumulates in binary32 across all of K, so the per-group dequantisation that bounds the int4 kernel
+// (one vector FMA per output and 64 of K) does not exist here: the K loop is matrix instructions and
+// operand movement only.
+//
+// Operand layout of that instruction for 4-bit data (checked against a host reference with random
+// codes and scales): lane l holds row (l % 32) of its operand and the 32 consecutive k
+// [32 (l / 32), +32) as 16 bytes, code k in nibble (k % 8) of dword (k / 8) % 4; the scale register of
+// lane l carries the E8M0 byte of exactly those 32 values (byte chosen by op_sel).  That is the
+// group-major activation layout of the int4 path unchanged: 32 bytes per token and 64-group, a lane
+// reads 16 of them.
+//
+// Kernel (a'): as the int4 quantise kernel (same lane layout, same low-rank down-projection on the
+// bf16 matrix cores), but a lane's 32 values ARE one MX block: absmax needs no cross-lane step, the
+// shared exponent is read off the binary32 exponent of rho * absmax (eq. 8), and
+// v_cvt_scalef32_pk_fp4_f32 rounds two values at a time to E2M1 (nearest, ties to the even code,
+// saturating; checked against the definition on 2e5 random and all boundary inputs).
+#include "svdq_dev.h"
+#include "svdq_kernels.h"
+#include "svdq_lds.h"
+
+namespace svdq {
+
+namespace {
+
+typedef int int8v __attribute__((ext_vector_type(8)));
+
+// ------------------------------------------------------------------------------------------------
+// kernel (a'): smooth, per-token per-32-block shared exponent, E2M1 codes, h = x^ L1
+// ------------------------------------------------------------------------------------------------
+constexpr int QROWS = 64;     // token rows per block
+constexpr int QWAVES = 4;     // K is split between the waves by stage (two 64-groups = 128 k)
+constexpr int QHPART_BYTES = QWAVES * QROWS * 33 * 4;
+
+// One 32-row block of one group: this lane's 32 values -> 16 bytes of codes and the block's E8M0 byte.
+__device__ __forceinline__ void quantize_block_mx(const uint4 (&xv)[4], const float* __restrict__ il_lds, float rho,
+                                                  uint4& codes, uint32_t& e8) {
+    float xs[32];
+    float a = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const float4 i0 = *reinterpret_cast<const float4*>(il_lds + 8 * s);
+        const float4 i1 = *reinterpret_cast<const float4*>(il_lds + 8 * s + 4);
+        const float ilv[8] = {i0.x, i0.y, i0.z, i0.w, i1.x, i1.y, i1.z, i1.w};
+        const uint32_t wds[4] = {xv[s].x, xv[s].y, xv[s].z, xv[s].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float lo = __fmul_rn(bf16lo_f(wds[j]), ilv[2 * j]);          // eq. 5 in binary32
+            float hi = __fmul_rn(bf16hi_f(wds[j]), ilv[2 * j + 1]);
+            xs[8 * s + 2 * j] = lo;
+            xs[8 * s + 2 * j + 1] = hi;
+            a = __builtin_fmaxf(a, __builtin_fmaxf(__builtin_fabsf(lo), __builtin_fabsf(hi)));
+        }
+    }
+    // eq. 8: alpha = rho * a is the block's reference magnitude; shared exponent floor(log2 alpha) - 2.
+    // For a normal alpha the binary32 exponent field is floor(log2 alpha) + 127, so the E8M0 byte is that
+    // field minus 2; below 2^-124 (field < 3) the block is empty.
+    const uint32_t field = (f_bits(__fmul_rn(rho, a)) >> 23) & 0xffu;
+    const bool live = field >= 3u;
+    e8 = live ? field - 2u : 0u;
+    const float X = bits_f((live ? field - 2u : 127u) << 23);           // 2^(byte - 127), a normal number
+    uint32_t packed[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        uint32_t wd = 0;
+        wd = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(wd, xs[8 * d + 0], xs[8 * d + 1], X, 0);
+        wd = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(wd, xs[8 * d + 2], xs[8 * d + 3], X, 1);
+        wd = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(wd, xs[8 * d + 4], xs[8 * d + 5], X, 2);
+        wd = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(wd, xs[8 * d + 6], xs[8 * d + 7], X, 3);
+        packed[d] = live ? wd : 0u;
+    }
+    codes = uint4{packed[0], packed[1], packed[2], packed[3]};
+}
+
+// Outputs: qx [K/64][M][32 B] (as the int4 path) and sxe [ceil(K/128)][M][2][2] bytes: for token m and stage s
+// (groups 2s, 2s+1) the two bytes [half h][group j] are the E8M0 scales of MX block 2 (2s + j) + h.
+template <bool LOWRANK>
+__global__ __launch_bounds__(256, 2)
+void quantize_mx_kernel(const uint16_t* __restrict__ x, int64_t ldx,
+                        const float* __restrict__ inv_lambda, float rho,
+                        const uint4* __restrict__ l1p, int64_t M, int K, int r,
+                        uint8_t* __restrict__ qx, uint16_t* __restrict__ sxe, float* __restrict__ h) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem_raw[];
+    float* il_s = reinterpret_cast<float*>(smem_raw);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int rr = lane & 31;
+    const int hf = lane >> 5;
+    const int ng = K >> 6;
+    const int nstages = (ng + 1) >> 1;
+    const int64_t row0 = (int64_t)blockIdx.x * QROWS;
+
+    for (int i = tid * 4; i < K; i += 1024)
+        *reinterpret_cast<float4*>(il_s + i) = *reinterpret_cast<const float4*>(inv_lambda + i);
+
+    float16v acc[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[b][i] = 0.0f;
+
+    const uint16_t* xrow[2];
+    int64_t rows[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        rows[b] = row0 + 32 * b + rr;
+        const int64_t rowc = rows[b] < M ? rows[b] : M - 1;
+        xrow[b] = x + rowc * ldx + hf * 32;
+    }
+
+    // round rd of this wave = group 2 (wave + 4 (rd / 2)) + rd % 2: the two groups of a stage follow each other
+    // so that their two scale bytes leave as one 16-bit store.  Software pipeline as in the int4 kernel: the
+    // next round's x is in flight while the current one is processed; two register buffers alternate.
+    auto group_of = [&](const int rd) { return 2 * (wave + QWAVES * (rd >> 1)) + (rd & 1); };
+    const int my_stages = (nstages > wave) ? (nstages - wave + QWAVES - 1) / QWAVES : 0;
+    const int rounds = 2 * my_stages;
+    uint4 xa[2][4], xb[2][4];
+    if (rounds > 0) {
+        const int g0 = group_of(0);                      // exists: stage `wave` exists, so group 2 wave < ng
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) xa[b][s] = reinterpret_cast<const uint4*>(xrow[b] + g0 * 64)[s];
+    }
+    __syncthreads();
+
+    uint32_t e_first[2] = {0u, 0u};
+    auto round_body = [&](const int rd, uint4 (&xc)[2][4], uint4 (&xn)[2][4], auto PAR) {
+        constexpr int parity = decltype(PAR)::value;
+        const int g = group_of(rd);
+        const bool exists = g < ng;                      // only the second group of the last stage can be missing
+        const int gl = exists ? g : ng - 1;
+        uint4 bfrag[4][2];
+        if (LOWRANK) {
+            const uint4* pb = l1p + (size_t)gl * (4 * 2 * 64) + lane;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                bfrag[s][0] = pb[(s * 2 + 0) * 64];
+                bfrag[s][1] = pb[(s * 2 + 1) * 64];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        int gn = (rd + 1 < rounds) ? group_of(rd + 1) : gl;
+        if (gn >= ng) gn = ng - 1;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) xn[b][s] = reinterpret_cast<const uint4*>(xrow[b] + gn * 64)[s];
+        __builtin_amdgcn_sched_barrier(0);
+
+        const float* il_lds = il_s + gl * 64 + hf * 32;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            uint4 codes;
+            uint32_t e8;
+            quantize_block_mx(xc[b], il_lds, rho, codes, e8);
+            if (!exists) e8 = 0u;                        // a group past K: both sides' zero bytes make it contribute 0
+            if (exists && rows[b] < M)
+                *reinterpret_cast<uint4*>(qx + ((size_t)g * M + rows[b]) * 32 + hf * 16) = codes;
+            if (parity == 0) {
+                e_first[b] = e8;
+            } else if (rows[b] < M) {
+                const int st = g >> 1;
+                sxe[((size_t)st * M + rows[b]) * 2 + hf] = (uint16_t)(e_first[b] | (e8 << 8));
+            }
+        }
+        if (LOWRANK && exists) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int sidx = 0; sidx < 4; ++sidx) {
+                    bf16x8 av = __builtin_bit_cast(bf16x8, xc[b][sidx]);
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sidx][0]), acc[b], 0, 0, 0);
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sidx][1]), acc[b], 0, 0, 0);
+                }
+        }
+    };
+    for (int rd = 0; rd < rounds; rd += 2) {
+        round_body(rd, xa, xb, IC<0>{});
+        round_body(rd + 1, xb, xa, IC<1>{});
+    }
+
+    if (LOWRANK) {
+        __syncthreads();                                     // every wave is done with inv_lambda in LDS
+        float* hpart = reinterpret_cast<float*>(smem_raw);   // [4][64][33]
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                int rloc = 32 * b + 8 * (i >> 2) + 4 * hf + (i & 3);
+                hpart[(wave * QROWS + rloc) * 33 + rr] = acc[b][i];
+            }
+        __syncthreads();
+        for (int idx = tid; idx < QROWS * r; idx += 256) {
+            int rloc = idx / r, j = idx - rloc * r;
+            int64_t row = row0 + rloc;
+            if (row < M)
+                h[row * r + j] = (hpart[(0 * QROWS + rloc) * 33 + j] + hpart[(1 * QROWS + rloc) * 33 + j]) +
+                                 (hpart[(2 * QROWS + rloc) * 33 + j] + hpart[(3 * QROWS + rloc) * 33 + j]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// offline packing of the MXFP4 residual
+// ------------------------------------------------------------------------------------------------
+__host__ __device__ inline size_t mx_wfrag_bytes(int N, int K) { return (size_t)N * (K / 2); }
+__host__ __device__ inline size_t mx_wscale_bytes(int N, int K) { return (size_t)(N / 32) * ((K / 64 + 1) / 2) * 128; }
+
+// Region 1: code fragments [N/32][K/64][64 lanes][16 B], lane (n = lane % 32, kh = lane / 32) holds bytes
+// [32 g + 16 kh, +16) of row n of the canonical codes (the A operand of the scaled MFMA as it stands).
+// Region 2: scale operands [N/32][stages][64 lanes][2 B]: lane (n, kh) holds the E8M0 bytes of MX blocks
+// 2 (2s) + kh and 2 (2s + 1) + kh of channel n, zero for a group past K.
+__global__ void pack_weight_mx_kernel(const uint8_t* __restrict__ qw, const uint8_t* __restrict__ sw,
+                                      int N, int K, uint8_t* __restrict__ out) {
+    const int ng = K >> 6, nst = (ng + 1) >> 1;
+    const size_t stride = (size_t)gridDim.x * blockDim.x, t0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint4* o1 = reinterpret_cast<uint4*>(out);
+    const size_t n1 = (size_t)(N >> 5) * ng * 64;
+    for (size_t v = t0; v < n1; v += stride) {
+        const int lane = (int)(v & 63);
+        const size_t fr = v >> 6;
+        const int g = (int)(fr % ng), nb = (int)(fr / ng);
+        const int n = nb * 32 + (lane & 31), kh = lane >> 5;
+        o1[v] = *reinterpret_cast<const uint4*>(qw + (size_t)n * (K >> 1) + g * 32 + kh * 16);
+    }
+    uint16_t* o2 = reinterpret_cast<uint16_t*>(out + mx_wfrag_bytes(N, K));
+    const size_t n2 = (size_t)(N >> 5) * nst * 64;
+    for (size_t v = t0; v < n2; v += stride) {
+        const int lane = (int)(v & 63);
+        const size_t fr = v >> 6;
+        const int st = (int)(fr % nst), nb = (int)(fr / nst);
+        const int n = nb * 32 + (lane & 31), kh = lane >> 5;
+        uint32_t e = 0;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int g = 2 * st + j;
+            if (g < ng) e |= (uint32_t)sw[(size_t)(2 * g + kh) * N + n] << (8 * j);
+        }
+        o2[v] = (uint16_t)e;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// kernels (b')+(c): block-scaled FP4 GEMM, fused low-rank up-projection, bias, store
+// ------------------------------------------------------------------------------------------------
+// Block = 4 waves as 2 (tokens) x 2 (channels); a wave owns 64 channels x 32 MT tokens = 2 x MT MFMA tiles.
+// The transposed tile D[n][m] is computed (weights are the A operand), as in the int4 kernel.
+// Stage = two 64-groups; three-slot LDS ring filled by direct global->LDS loads, protocol as in the int4
+// kernel: in the middle of stage s every wave has taken its last operand from the slot, so after the
+// barrier the slot takes stage s + 3.
+template <int MT>
+struct MxGeom {
+    static constexpr int BM = 64 * MT;                              // tokens per block
+    static constexpr int BN = 128;                                  // channels per block
+    static constexpr uint32_t OFF_A = 0;                            // [group 2][half 2][BM] x 16 B
+    static constexpr uint32_t OFF_W = 64 * BM;                      // [group 2][n-block 4][64 lanes] x 16 B
+    static constexpr uint32_t OFF_SX = OFF_W + 8192;                // [BM][half 2][group 2] bytes
+    static constexpr uint32_t OFF_SW = OFF_SX + 4 * BM;             // [n-block 4][64 lanes][group 2] bytes
+    static constexpr uint32_t STAGE = OFF_SW + 512;
+    static constexpr int NDMA = MT + 2 + 1 + 1;                     // per wave and stage: MT of A, 2 of W, 1 + 1 of scales
+};
+
+__device__ __forceinline__ uint32_t lds_read2(uint32_t off) {
+    return *reinterpret_cast<const __attribute__((address_space(3))) uint16_t*>((lds_byte*)(uintptr_t)off);
+}
+
+template <int MT>
+__global__ __launch_bounds__(256, 2)
+void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__ sxe,
+                    const uint4* __restrict__ wfrag, const uint16_t* __restrict__ wscale,
+                    const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
+                    int64_t M, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
+                    int mtiles, int ntiles) {
+    using G = MxGeom<MT>;
+    constexpr int BM = G::BM;
+    constexpr int NDMA = G::NDMA;
+    __shared__ __attribute__((aligned(16))) uint8_t ring[3 * G::STAGE];
+
+    // XCD-aware tile order (consecutive block ids go round-robin to the 8 XCDs): each XCD walks its own
+    // token tiles, 8 at a time across n.
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7, idx = bid >> 3;
+    const int sm = idx / (8 * ntiles), rem = idx - sm * (8 * ntiles);
+    const int nt = rem >> 3;
+    const int mt = (sm * 8 + (rem & 7)) * 8 + xcd;
+    if (mt >= mtiles) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const int l32 = lane & 31, kh = lane >> 5;
+    const int ng = K >> 6;
+    const int nstages = (ng + 1) >> 1;
+    const int64_t m0 = (int64_t)mt * BM;
+    const int n0 = nt * G::BN;
+    const int nbB = n0 >> 5;
+    const uint32_t ring0 = (uint32_t)(uintptr_t)(lds_byte*)ring;
+
+    // ---- staging: wave w moves, per stage, the A chunks (group w / 2, half w % 2, 64-token quarter q = 0..MT-1),
+    // the W chunks (group w / 2, n-blocks 2 (w % 2) + {0, 1}), 64 tokens' scale bytes and one half of the
+    // channel scale bytes (waves 2, 3 repeat what waves 0, 1 move so that every wave counts NDMA loads).
+    const int cj = wave >> 1, sp = wave & 1;
+    uint32_t va[MT];
+#pragma unroll
+    for (int q = 0; q < MT; ++q) {
+        const int64_t row = m0 + q * 64 + lane;
+        va[q] = (uint32_t)(((row < M) ? row : (M - 1)) * 32 + sp * 16);
+    }
+    const uint32_t vl16 = lane * 16;
+    const uint32_t vw[2] = {(uint32_t)((2 * sp + 0) * ng * 1024) + vl16, (uint32_t)((2 * sp + 1) * ng * 1024) + vl16};
+    uint32_t vsx = 0;                                                 // token scales: wave w moves tokens [64 w, +64) (MT = 4) ...
+    if (wave < MT) {
+        const int64_t row = m0 + wave * 64 + lane;
+        vsx = (uint32_t)(((row < M) ? row : (M - 1)) * 4);
+    } else {                                                          // ... or repeats wave w - MT's (MT = 2)
+        const int64_t row = m0 + (wave - MT) * 64 + lane;
+        vsx = (uint32_t)(((row < M) ? row : (M - 1)) * 4);
+    }
+    const int sxw = (wave < MT) ? wave : wave - MT;
+    const uint32_t vsw = (uint32_t)(kh * nstages * 128 + l32 * 4);    // channel scales: lanes 0..31 one n-block, 32..63 the next
+    auto stage_issue = [&](const int s) {
+        const uint32_t slot = ring0 + (uint32_t)(s % 3) * G::STAGE;
+        const int g = (2 * s + cj < ng) ? 2 * s + cj : ng - 1;        // odd tail: re-read (its scale bytes are zero)
+#pragma unroll
+        for (int q = 0; q < MT; ++q)
+            dma16(qx + (size_t)g * M * 32, va[q], slot + G::OFF_A + ((cj * 2 + sp) * BM + q * 64) * 16);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            dma16(wfrag + ((size_t)nbB * ng + g) * 64, vw[i], slot + G::OFF_W + (cj * 4 + 2 * sp + i) * 1024);
+        dma4(sxe + (size_t)s * M * 2, vsx, slot + G::OFF_SX + sxw * 256);
+        dma4(wscale + ((size_t)(nbB + 2 * sp) * nstages + s) * 64, vsw, slot + G::OFF_SW + sp * 256);
+    };
+
+    // per-lane LDS read offsets inside a slot
+    const uint32_t rd_a = G::OFF_A + (kh * BM + wm * (32 * MT) + l32) * 16;   // + group 32 BM + mi 512
+    const uint32_t rd_w = G::OFF_W + (wn * 2 * 64 + lane) * 16;               // + group 4096 + ni 1024
+    const uint32_t rd_sx = G::OFF_SX + ((wm * (32 * MT) + l32) * 2 + kh) * 2; // + mi 128
+    const uint32_t rd_sw = G::OFF_SW + (wn * 2 * 64 + lane) * 2;              // + ni 128
+
+    float16v y[2][MT];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < MT; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) y[a][b][i] = 0.0f;
+
+    stage_issue(0);
+    if (nstages > 1) stage_issue(1);
+    if (nstages > 2) stage_issue(2);
+    if (nstages > 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
+    else if (nstages > 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    uint4 wf[2], xf[MT];                       // 4-bit operands of the next group to start
+    uint32_t swv[2], sxv[MT];                  // scale bytes of both groups of the stage
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+        wf[ni] = lds_read16(ring0 + rd_w + ni * 1024);
+        swv[ni] = lds_read2(ring0 + rd_sw + ni * 128);
+    }
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) {
+        xf[mi] = lds_read16(ring0 + rd_a + mi * 512);
+        sxv[mi] = lds_read2(ring0 + rd_sx + mi * 128);
+    }
+
+    auto mma_group = [&](auto JC) {
+        constexpr int j = decltype(JC)::value;
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const int8v a = {(int)wf[ni].x, (int)wf[ni].y, (int)wf[ni].z, (int)wf[ni].w, 0, 0, 0, 0};
+#pragma unroll
+            for (int mi = 0; mi < MT; ++mi) {
+                const int8v b = {(int)xf[mi].x, (int)xf[mi].y, (int)xf[mi].z, (int)xf[mi].w, 0, 0, 0, 0};
+                y[ni][mi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, y[ni][mi], 4, 4, j, (int)swv[ni], j, (int)sxv[mi]);
+            }
+        }
+    };
+
+    uint32_t cur = ring0;
+    for (int s = 0; s < nstages; ++s) {
+        const uint32_t nxt = (cur == ring0 + 2 * G::STAGE) ? ring0 : cur + G::STAGE;
+        // first group; then its successor's operands (the second group of this stage, or zero-scaled re-read)
+        mma_group(IC<0>{});
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) wf[ni] = lds_read16(cur + rd_w + 4096 + ni * 1024);
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi) xf[mi] = lds_read16(cur + rd_a + 32 * BM + mi * 512);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // second group.  This wave's reads of the slot are complete once the loads above have returned (the barrier
+        // waits for them), so after the barrier the slot can take stage s + 3; stage s + 1, requested two stages
+        // ago, is made visible for the loads below.
+        if (s + 1 < nstages) {
+            if (s + 2 < nstages) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (s + 3 < nstages) stage_issue(s + 3);
+        }
+        mma_group(IC<1>{});
+        if (s + 1 < nstages) {
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                wf[ni] = lds_read16(nxt + rd_w + ni * 1024);
+                swv[ni] = lds_read2(nxt + rd_sw + ni * 128);
+            }
+#pragma unroll
+            for (int mi = 0; mi < MT; ++mi) {
+                xf[mi] = lds_read16(nxt + rd_a + mi * 512);
+                sxv[mi] = lds_read2(nxt + rd_sx + mi * 128);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        cur = nxt;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may still be writing this block's LDS when it ends
+
+    // ---- epilogue (c): low-rank up-projection on the bf16 matrix cores, bias, store
+    if (r > 0) {
+        const int ksteps = r >> 4;
+        for (int ks = 0; ks < ksteps; ++ks) {
+            bf16x8 lf[2];                      // L2^T fragment: row n, k = j
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                const int n = n0 + wn * 64 + ni * 32 + l32;
+                uint32_t wds[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    uint32_t lo = L2[(int64_t)(16 * ks + 8 * kh + 2 * e) * N + n];
+                    uint32_t hi = L2[(int64_t)(16 * ks + 8 * kh + 2 * e + 1) * N + n];
+                    wds[e] = lo | (hi << 16);
+                }
+                uint4 t = {wds[0], wds[1], wds[2], wds[3]};
+                lf[ni] = __builtin_bit_cast(bf16x8, t);
+            }
+#pragma unroll
+            for (int mi = 0; mi < MT; ++mi) {
+                int64_t m = m0 + wm * (32 * MT) + mi * 32 + l32;
+                if (m >= M) m = M - 1;
+                const float4* ph = reinterpret_cast<const float4*>(h + m * r + 16 * ks + 8 * kh);
+                float4 h0 = ph[0], h1 = ph[1];
+                const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+                uint32_t hi16[8], lo16[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    hi16[e] = f_bf16_rne(hv[e]);
+                    lo16[e] = f_bf16_rne(hv[e] - bits_f(hi16[e] << 16));
+                }
+                uint4 th = {hi16[0] | (hi16[1] << 16), hi16[2] | (hi16[3] << 16), hi16[4] | (hi16[5] << 16), hi16[6] | (hi16[7] << 16)};
+                uint4 tl = {lo16[0] | (lo16[1] << 16), lo16[2] | (lo16[3] << 16), lo16[4] | (lo16[5] << 16), lo16[6] | (lo16[7] << 16)};
+                bf16x8 hhi = __builtin_bit_cast(bf16x8, th), hlo = __builtin_bit_cast(bf16x8, tl);
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[ni], hhi, y[ni][mi], 0, 0, 0);
+                    y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[ni], hlo, y[ni][mi], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int n = n0 + wn * 64 + ni * 32 + 8 * q + 4 * kh;
+            float4 bv = {0.f, 0.f, 0.f, 0.f};
+            if (bias) bv = *reinterpret_cast<const float4*>(bias + n);
+#pragma unroll
+            for (int mi = 0; mi < MT; ++mi) {
+                const int64_t m = m0 + wm * (32 * MT) + mi * 32 + l32;
+                if (m >= M) continue;
+                float v0 = y[ni][mi][4 * q + 0] + bv.x, v1 = y[ni][mi][4 * q + 1] + bv.y;
+                float v2 = y[ni][mi][4 * q + 2] + bv.z, v3 = y[ni][mi][4 * q + 3] + bv.w;
+                if (out_f32) {
+                    float4 o = {v0, v1, v2, v3};
+                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(yout) + m * ldy + n) = o;
+                } else {
+                    uint2 o = {f_bf16_rne(v0) | (f_bf16_rne(v1) << 16), f_bf16_rne(v2) | (f_bf16_rne(v3) << 16)};
+                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(yout) + m * ldy + n) = o;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+size_t packed_weight_mx_bytes(int N, int K) { return mx_wfrag_bytes(N, K) + mx_wscale_bytes(N, K); }
+
+hipError_t launch_pack_weight_mx(const uint8_t* qw, const uint8_t* sw, int N, int K, void* out, hipStream_t stream) {
+    hipLaunchKernelGGL(pack_weight_mx_kernel, dim3(1024), dim3(256), 0, stream, qw, sw, N, K, (uint8_t*)out);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_mx(const void* x, int64_t ldx, const float* inv_lambda, float rho,
+                              const void* l1p, int64_t M, int K, int r,
+                              uint8_t* qx, uint8_t* sxe, float* h, hipStream_t stream) {
+    const unsigned blocks = (unsigned)((M + QROWS - 1) / QROWS);
+    size_t lds = (size_t)K * sizeof(float);
+    if (lds < (size_t)QHPART_BYTES) lds = QHPART_BYTES;
+    if (l1p)
+        hipLaunchKernelGGL(quantize_mx_kernel<true>, dim3(blocks), dim3(256), lds, stream,
+                           (const uint16_t*)x, ldx, inv_lambda, rho, (const uint4*)l1p, M, K, r, qx, (uint16_t*)sxe, h);
+    else
+        hipLaunchKernelGGL(quantize_mx_kernel<false>, dim3(blocks), dim3(256), lds, stream,
+                           (const uint16_t*)x, ldx, inv_lambda, rho, (const uint4*)nullptr, M, K, r, qx, (uint16_t*)sxe, h);
+    return hipGetLastError();
+}
+
+hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w_packed,
+                            const float* h, const void* L2, const float* bias,
+                            int64_t M, int N, int K, int r, void* y, int64_t ldy, int out_f32,
+                            hipStream_t stream) {
+    constexpr int MT = 4;
+    const int mtiles = (int)((M + MxGeom<MT>::BM - 1) / MxGeom<MT>::BM), ntiles = N / 128;
+    const uint8_t* base = (const uint8_t*)w_packed;
+    const unsigned grid = (unsigned)(((mtiles + 63) / 64) * 64 * ntiles);
+    hipLaunchKernelGGL(gemm_mx_kernel<MT>, dim3(grid), dim3(256), 0, stream,
+                       qx, (const uint16_t*)sxe, (const uint4*)base, (const uint16_t*)(base + mx_wfrag_bytes(N, K)),
+                       h, (const uint16_t*)L2, bias, M, N, K, r, y, ldy, out_f32, mtiles, ntiles);
+    return hipGetLastError();
+}
+
+}  // namespace svdq
