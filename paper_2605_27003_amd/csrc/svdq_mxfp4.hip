@@ -358,66 +358,74 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    uint4 wf[2], xf[MT];                       // 4-bit operands of the next group to start
-    uint32_t swv[2], sxv[MT];                  // scale bytes of both groups of the stage
+    // Two operand register sets: set 0 feeds the first group of a stage (scale byte 0 of each 16-bit scale
+    // entry), set 1 the second (byte 1).  Each set is requested from LDS one group ahead of its MFMAs, so the
+    // loads of one group land while the other group's eight matrix instructions run.
+    struct Operands {
+        uint4 wf[2], xf[MT];
+        uint32_t sw[2], sx[MT];
+    };
+    Operands op0, op1;
+    auto fetch = [&](Operands& o, const uint32_t slot, const int j) {
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
-        wf[ni] = lds_read16(ring0 + rd_w + ni * 1024);
-        swv[ni] = lds_read2(ring0 + rd_sw + ni * 128);
-    }
+        for (int ni = 0; ni < 2; ++ni) {
+            o.wf[ni] = lds_read16_pinned(slot + rd_w + j * 4096 + ni * 1024);
+            o.sw[ni] = lds_read2_pinned(slot + rd_sw + ni * 128);
+        }
 #pragma unroll
-    for (int mi = 0; mi < MT; ++mi) {
-        xf[mi] = lds_read16(ring0 + rd_a + mi * 512);
-        sxv[mi] = lds_read2(ring0 + rd_sx + mi * 128);
-    }
-
-    auto mma_group = [&](auto JC) {
+        for (int mi = 0; mi < MT; ++mi) {
+            o.xf[mi] = lds_read16_pinned(slot + rd_a + j * 32 * BM + mi * 512);
+            o.sx[mi] = lds_read2_pinned(slot + rd_sx + mi * 128);
+        }
+    };
+    auto mma_group = [&](const Operands& o, auto JC) {
         constexpr int j = decltype(JC)::value;
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) {
-            const int8v a = {(int)wf[ni].x, (int)wf[ni].y, (int)wf[ni].z, (int)wf[ni].w, 0, 0, 0, 0};
+            const int8v a = {(int)o.wf[ni].x, (int)o.wf[ni].y, (int)o.wf[ni].z, (int)o.wf[ni].w, 0, 0, 0, 0};
 #pragma unroll
             for (int mi = 0; mi < MT; ++mi) {
-                const int8v b = {(int)xf[mi].x, (int)xf[mi].y, (int)xf[mi].z, (int)xf[mi].w, 0, 0, 0, 0};
-                y[ni][mi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, y[ni][mi], 4, 4, j, (int)swv[ni], j, (int)sxv[mi]);
+                const int8v b = {(int)o.xf[mi].x, (int)o.xf[mi].y, (int)o.xf[mi].z, (int)o.xf[mi].w, 0, 0, 0, 0};
+                y[ni][mi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, y[ni][mi], 4, 4, j, (int)o.sw[ni], j, (int)o.sx[mi]);
             }
         }
     };
 
-    uint32_t cur = ring0;
-    for (int s = 0; s < nstages; ++s) {
-        const uint32_t nxt = (cur == ring0 + 2 * G::STAGE) ? ring0 : cur + G::STAGE;
-        // first group; then its successor's operands (the second group of this stage, or zero-scaled re-read)
-        mma_group(IC<0>{});
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni) wf[ni] = lds_read16(cur + rd_w + 4096 + ni * 1024);
-#pragma unroll
-        for (int mi = 0; mi < MT; ++mi) xf[mi] = lds_read16(cur + rd_a + 32 * BM + mi * 512);
+    // One stage.  FULL: stages s+1..s+3 exist, so the body is straight-line code (the compiler otherwise sinks
+    // the first group's matrix instructions past the conditional blocks, next to the second group's).
+    auto stage_body = [&](const int s, const uint32_t cur, const uint32_t nxt, auto FULLC) {
+        constexpr bool FULL = decltype(FULLC)::value;
+        // second group's operands requested, first group multiplied
+        fetch(op1, cur, 1);
         __builtin_amdgcn_sched_barrier(0);
-
-        // second group.  This wave's reads of the slot are complete once the loads above have returned (the barrier
-        // waits for them), so after the barrier the slot can take stage s + 3; stage s + 1, requested two stages
-        // ago, is made visible for the loads below.
-        if (s + 1 < nstages) {
-            if (s + 2 < nstages) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
+        mma_group(op0, IC<0>{});
+        __builtin_amdgcn_sched_barrier(0);
+        // This wave has now requested everything it needs from the slot (the barrier waits for the loads to
+        // return), so after the barrier the slot can take stage s + 3; stage s + 1, requested two stages ago, is
+        // made visible for the fetch below.
+        if (FULL || s + 1 < nstages) {
+            if (FULL || s + 2 < nstages) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            if (s + 3 < nstages) stage_issue(s + 3);
-        }
-        mma_group(IC<1>{});
-        if (s + 1 < nstages) {
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                wf[ni] = lds_read16(nxt + rd_w + ni * 1024);
-                swv[ni] = lds_read2(nxt + rd_sw + ni * 128);
-            }
-#pragma unroll
-            for (int mi = 0; mi < MT; ++mi) {
-                xf[mi] = lds_read16(nxt + rd_a + mi * 512);
-                sxv[mi] = lds_read2(nxt + rd_sx + mi * 128);
-            }
+            if (FULL || s + 3 < nstages) stage_issue(s + 3);
+            fetch(op0, nxt, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
+        mma_group(op1, IC<1>{});
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    fetch(op0, ring0, 0);
+    uint32_t cur = ring0;
+    auto next_slot = [&](const uint32_t c) { return (c == ring0 + 2 * G::STAGE) ? ring0 : c + G::STAGE; };
+    int s = 0;
+    for (; s + 3 < nstages; ++s) {
+        const uint32_t nxt = next_slot(cur);
+        stage_body(s, cur, nxt, IC<1>{});
+        cur = nxt;
+    }
+    for (; s < nstages; ++s) {
+        const uint32_t nxt = next_slot(cur);
+        stage_body(s, cur, nxt, IC<0>{});
         cur = nxt;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may still be writing this block's LDS when it ends
@@ -465,8 +473,9 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
         }
     }
 
+    // bias: channel n = 8 q + 4 kh + (i % 4) of the 32-channel tile
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
+    for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int n = n0 + wn * 64 + ni * 32 + 8 * q + 4 * kh;
@@ -474,19 +483,32 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
             if (bias) bv = *reinterpret_cast<const float4*>(bias + n);
 #pragma unroll
             for (int mi = 0; mi < MT; ++mi) {
-                const int64_t m = m0 + wm * (32 * MT) + mi * 32 + l32;
-                if (m >= M) continue;
-                float v0 = y[ni][mi][4 * q + 0] + bv.x, v1 = y[ni][mi][4 * q + 1] + bv.y;
-                float v2 = y[ni][mi][4 * q + 2] + bv.z, v3 = y[ni][mi][4 * q + 3] + bv.w;
-                if (out_f32) {
-                    float4 o = {v0, v1, v2, v3};
-                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(yout) + m * ldy + n) = o;
-                } else {
-                    uint2 o = {f_bf16_rne(v0) | (f_bf16_rne(v1) << 16), f_bf16_rne(v2) | (f_bf16_rne(v3) << 16)};
-                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(yout) + m * ldy + n) = o;
-                }
+                y[ni][mi][4 * q + 0] += bv.x;
+                y[ni][mi][4 * q + 1] += bv.y;
+                y[ni][mi][4 * q + 2] += bv.z;
+                y[ni][mi][4 * q + 3] += bv.w;
             }
         }
+    const int64_t mw = m0 + wm * (32 * MT);                   // first token of this wave's tile
+    if (out_f32) {
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * 64 + ni * 32 + 8 * q + 4 * kh;
+#pragma unroll
+                for (int mi = 0; mi < MT; ++mi) {
+                    const int64_t m = mw + mi * 32 + l32;
+                    if (m >= M) continue;
+                    float4 o = {y[ni][mi][4 * q + 0], y[ni][mi][4 * q + 1], y[ni][mi][4 * q + 2], y[ni][mi][4 * q + 3]};
+                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(yout) + m * ldy + n) = o;
+                }
+            }
+    } else {
+        __syncthreads();                                       // every wave is done with the operand ring
+        store_tile_bf16<MT>([&](int ni, int mi, int i) { return y[ni][mi][i]; },
+                            ring0 + wave * (32 * MT) * YROW, lane,
+                            reinterpret_cast<uint16_t*>(yout) + mw * ldy + n0 + wn * 64, ldy, M - mw);
     }
 }
 
