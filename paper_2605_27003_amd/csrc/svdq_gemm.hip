@@ -410,8 +410,9 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
         }
     }
 
+    // bias: channel n = 8 q + 4 kh + (i % 4) of the 32-channel tile
 #pragma unroll
-    for (int ni = 0; ni < 2; ++ni) {
+    for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int n = n0 + wn * 64 + ni * 32 + 8 * q + 4 * kh;
@@ -419,19 +420,32 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
             if (bias) bv = *reinterpret_cast<const float4*>(bias + n);
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi) {
-                const int64_t m = m0 + wm * 64 + mi * 32 + l32;
-                if (m >= M) continue;
-                float v0 = y[ni][mi][4 * q + 0] + bv.x, v1 = y[ni][mi][4 * q + 1] + bv.y;
-                float v2 = y[ni][mi][4 * q + 2] + bv.z, v3 = y[ni][mi][4 * q + 3] + bv.w;
-                if (out_f32) {
-                    float4 o = {v0, v1, v2, v3};
-                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(yout) + m * ldy + n) = o;
-                } else {
-                    uint2 o = {f_bf16_rne(v0) | (f_bf16_rne(v1) << 16), f_bf16_rne(v2) | (f_bf16_rne(v3) << 16)};
-                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(yout) + m * ldy + n) = o;
-                }
+                y[ni][mi][4 * q + 0] += bv.x;
+                y[ni][mi][4 * q + 1] += bv.y;
+                y[ni][mi][4 * q + 2] += bv.z;
+                y[ni][mi][4 * q + 3] += bv.w;
             }
         }
+    const int64_t mw = m0 + wm * 64;                           // first token of this wave's tile
+    if (out_f32) {
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * 64 + ni * 32 + 8 * q + 4 * kh;
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) {
+                    const int64_t m = mw + mi * 32 + l32;
+                    if (m >= M) continue;
+                    float4 o = {y[ni][mi][4 * q + 0], y[ni][mi][4 * q + 1], y[ni][mi][4 * q + 2], y[ni][mi][4 * q + 3]};
+                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(yout) + m * ldy + n) = o;
+                }
+            }
+    } else {
+        __syncthreads();                                       // every wave is done with the operand ring
+        store_tile_bf16<2>([&](int ni, int mi, int i) { return y[ni][mi][i]; },
+                           ring0 + wave * 64 * YROW, lane,
+                           reinterpret_cast<uint16_t*>(yout) + mw * ldy + n0 + wn * 64, ldy, M - mw);
     }
 }
 
