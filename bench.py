@@ -5,7 +5,9 @@ the fused quantise kernel (smooth, absmax, clipped int4 quantise/pack, x^ L1)
 followed by the W4A4 GEMM with its fused low-rank/bias/bf16 epilogue, on the
 Wan2.2-shaped attention output projection (M=32760, K=N=5120, r=32); the
 clipping ratio cycles through the layer's four timestep bins.  Inputs are
-resident in HBM before the timed region.  Prints ONE JSON line.
+resident in HBM before the timed region.  Prints ONE JSON line; its headline
+fields are the int4 path, "mxfp4_variant" carries the same layer in the MXFP4
+format and "context" a dense bf16 GEMM of the same shape.
 """
 import argparse
 import json
@@ -67,6 +69,7 @@ def main():
                     help="untimed steps; the clocks need some tens of launches after idle to settle")
     ap.add_argument("--workload", type=int, default=1, help="index into the five configurations (default: the metric's)")
     ap.add_argument("--cpu-rows", type=int, default=12288, help="token rows of the CPU-oracle baseline sample (0 = skip)")
+    ap.add_argument("--skip-mxfp4", action="store_true", help="do not also time the MXFP4 variant of the layer")
     ap.add_argument("--xsets", type=int, default=3, help="input buffer sets rotated so caches cannot hold the working set")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -85,46 +88,75 @@ def main():
     torch.cuda.set_device(0)
     svdq.load_library(build_if_missing=False)
 
-    w = synth.workload(args.workload)
-    lname = sorted(w.layers)[0]
-    L = w.layers[lname]
-    xname = w.inputs_of[lname.split("/")[1]]
-    table = w.tables[lname.split("/")[0]]
-    M, K, N, r = w.M, L.K, L.N, L.r
+    FP4_MFMA_PEAK_TFLOPS = 10100.0    # MI355X dense fp4 matrix peak
 
-    lin = svdq.W4A4Linear(dev(L.inv_lambda), dev(L.L1), dev(L.L2), dev(L.qw), dev(L.sw), dev(L.bias))
-    x0 = dev(w.x[xname])
-    xs = [x0] + [x0.roll(17 * (i + 1), dims=0).contiguous() for i in range(args.xsets - 1)]
-    qx, sx, h, y = lin.buffers(M, x0.device)
-    ysets = [y] + [torch.empty_like(y) for _ in range(args.xsets - 1)]
+    def measure(fmt):
+        """One pass of the hot path per step for the given 4-bit format; returns the timing record."""
+        w = synth.workload(args.workload, fmt=fmt)
+        lname = sorted(w.layers)[0]
+        L = w.layers[lname]
+        xname = w.inputs_of[lname.split("/")[1]]
+        table = w.tables[lname.split("/")[0]]
+        M, K, N, r = w.M, L.K, L.N, L.r
+        inv_lambda, L2, bias = dev(L.inv_lambda), dev(L.L2), dev(L.bias)
+        l1p = svdq.pack_lowrank_down(dev(L.L1), inv_lambda)
+        x0 = dev(w.x[xname])
+        xs = [x0] + [x0.roll(17 * (i + 1), dims=0).contiguous() for i in range(args.xsets - 1)]
+        ysets = [torch.empty((M, N), dtype=torch.bfloat16, device=x0.device) for _ in range(args.xsets)]
+        h = torch.empty((M, r), dtype=torch.float32, device=x0.device)
+        qx = torch.empty((K // 64, M, 32), dtype=torch.uint8, device=x0.device)
+        if fmt == "int4":
+            wp = svdq.pack_weight(dev(L.qw), dev(L.sw))
+            sx = torch.empty((K // 64, M), dtype=torch.float32, device=x0.device)
+            quant, gemm = svdq.quantize_act, svdq.linear_w4a4
+            scale_bytes = 4 * (K // 64)
+        else:
+            wp = svdq.pack_weight_mxfp4(dev(L.qw), dev(L.sw))
+            sx = torch.empty(((K // 64 + 1) // 2, M, 2, 2), dtype=torch.uint8, device=x0.device)
+            quant, gemm = svdq.quantize_act_mxfp4, svdq.linear_mxfp4
+            scale_bytes = K // 32
 
-    def step(i, ev=None):
-        rho = table[i % len(table)]
-        if ev:
-            ev[0].record()
-        svdq.quantize_act(xs[i % len(xs)], lin.inv_lambda, rho, lin.l1_packed, r, out=(qx, sx, h))
-        if ev:
-            ev[1].record()
-        svdq.linear_w4a4(qx, sx, lin.w_packed, N, h, lin.L2, lin.bias, out=ysets[i % len(ysets)])
-        if ev:
-            ev[2].record()
+        def step(i, ev=None):
+            rho = table[i % len(table)]
+            if ev:
+                ev[0].record()
+            quant(xs[i % len(xs)], inv_lambda, rho, l1p, r, out=(qx, sx, h))
+            if ev:
+                ev[1].record()
+            gemm(qx, sx, wp, N, h, L2, bias, out=ysets[i % len(ysets)])
+            if ev:
+                ev[2].record()
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i, events[i])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i, events[i])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_step = (t1 - t0) * 1e3 / args.steps
+        tq = np.array([e[0].elapsed_time(e[1]) for e in events])          # ms, kernel (a)
+        tg = np.array([e[1].elapsed_time(e[2]) for e in events])          # ms, kernels (b)+(c)
+        # dense bf16 GEMM of the same shape from the vendor library: what the paper's BF16 baseline costs here
+        wd = torch.empty((K, N), dtype=torch.bfloat16, device=x0.device).normal_()
+        for _ in range(5):
+            torch.matmul(xs[0], wd, out=ysets[0])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(20):
+            torch.matmul(xs[i % len(xs)], wd, out=ysets[i % len(ysets)])
+        e1.record()
+        torch.cuda.synchronize()
+        return dict(w=w, L=L, table=table, M=M, K=K, N=N, r=r, ms_step=ms_step, tq=tq, tg=tg, nx=len(xs),
+                    ops=2.0 * M * N * K, bytes_q=M * (2 * K + K // 2 + scale_bytes + 4 * r),
+                    bf16_ms=e0.elapsed_time(e1) / 20)
 
-    ms_step = (t1 - t0) * 1e3 / args.steps
-    tq = np.array([e[0].elapsed_time(e[1]) for e in events])          # ms, kernel (a)
-    tg = np.array([e[1].elapsed_time(e[2]) for e in events])          # ms, kernels (b)+(c)
-    ops = 2.0 * M * N * K
-    bytes_q = M * (2 * K + K // 2 + 4 * K // 64 + 4 * r)              # read x, write codes, scales, h
+    R = measure("int4")
+    w, L, table, M, K, N, r = R["w"], R["L"], R["table"], R["M"], R["K"], R["N"], R["r"]
+    ops, bytes_q, tq, tg, ms_step = R["ops"], R["bytes_q"], R["tq"], R["tg"], R["ms_step"]
     gemm_tops = ops / (tg.mean() * 1e-3) / 1e12
     quant_gbs = bytes_q / (tq.mean() * 1e-3) / 1e9
 
@@ -135,7 +167,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int4 x int4 -> int32 (int8 MFMA), fp32 dequant, bf16 out", "data": "synthetic",
         "config": {"workload": f"{w.name}: M={M} K={K} N={N} r={r} group=64, rho per timestep bin {table}",
-                   "step": "svdq_quantize_act + svdq_linear_w4a4", "input_sets": len(xs)},
+                   "step": "svdq_quantize_act + svdq_linear_w4a4", "input_sets": R["nx"]},
         "roofline": {"kernel": "svdq_linear_w4a4 (gemm_kernel)", "bound": "mfma",
                      "achieved": gemm_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": gemm_tops / INT8_MFMA_PEAK_TOPS,
@@ -146,8 +178,27 @@ def main():
                               "frac": quant_gbs / HBM_PEAK_GBS,
                               "traffic": measured_traffic(w.name, "quantize_kernel"),
                               "algorithmic_bytes": bytes_q, "avg_ms": float(tq.mean()), "min_ms": float(tq.min())},
+        "context": {"bf16_dense_matmul_ms": R["bf16_ms"],
+                    "note": "vendor-library bf16 GEMM of the same shape on the same GPU (the paper's BF16 baseline)"},
     }
-    del xs, ysets
+    if not args.skip_mxfp4:
+        X = measure("mxfp4")
+        g = X["ops"] / (X["tg"].mean() * 1e-3) / 1e12
+        q = X["bytes_q"] / (X["tq"].mean() * 1e-3) / 1e9
+        out["mxfp4_variant"] = {
+            "what": "same layer in the MXFP4 format of the paper's Table I on the block-scaled FP4 matrix instruction",
+            "value": X["ops"] / (X["ms_step"] * 1e-3) / 1e12, "unit": "TFLOP/s", "ms_per_step": X["ms_step"],
+            "roofline": {"kernel": "svdq_linear_mxfp4 (gemm_mx_kernel)", "bound": "mfma", "achieved": g,
+                         "peak": FP4_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": g / FP4_MFMA_PEAK_TFLOPS,
+                         "traffic": measured_traffic(w.name, "gemm_mx_kernel"),
+                         "avg_ms": float(X["tg"].mean()), "min_ms": float(X["tg"].min())},
+            "roofline_quantize": {"kernel": "svdq_quantize_act_mxfp4 (quantize_mx_kernel)", "bound": "hbm",
+                                  "achieved": q, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": q / HBM_PEAK_GBS,
+                                  "traffic": measured_traffic(w.name, "quantize_mx_kernel"),
+                                  "algorithmic_bytes": X["bytes_q"], "avg_ms": float(X["tq"].mean()),
+                                  "min_ms": float(X["tq"].min())},
+            "speedup_vs_bf16_dense": X["bf16_ms"] / X["ms_step"]}
+        del X
     if args.cpu_rows > 0:
         out["cpu_baseline"] = cpu_baseline(w, L, args.cpu_rows)
     print(json.dumps(out))
