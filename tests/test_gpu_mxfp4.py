@@ -120,3 +120,36 @@ def test_determinism_and_guard_bands(svdq):
         assert torch.equal(a, b)
     for buf, val in ((qbuf, 0xAB), (sbuf, 0xCD), (hbuf, -7.0), (ybuf, -7.0)):
         assert torch.all(buf[:pad] == val) and torch.all(buf[-pad:] == val)
+
+
+# ---------------------------------------------------------------------------------------------
+# full sizes, in the launch configuration bench.py times
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("idx", [1, 2, 3])
+def test_full_size_configs(svdq, oracle, idx):
+    """Codes and scale bytes over the WHOLE buffers (bit-exact), h on a row sample, y (bf16 and the pre-rounding
+    binary32 value) on a seeded row sample: first 64, last 64 (ragged last tile), random rows."""
+    from tests.helpers import rel_fro
+    w = synth.workload(idx, fmt="mxfp4")
+    L, x = w.layers["e0/lin"], w.x["x"]
+    M, K = x.shape
+    DL = MxLayer(svdq, L)
+    rho = w.tables["e0"][0]
+    qx, sx, h = svdq.quantize_act_mxfp4(dev(x), DL.inv_lambda, rho, DL.l1p, L.r)
+    y16 = svdq.linear_mxfp4(qx, sx, DL.wp, L.N, h, DL.L2, DL.bias)
+    torch.cuda.synchronize()
+    fq, fs = oracle.quantize_act_mxfp4(x, L.inv_lambda, rho)
+    gq, gs = svdq.mx_to_token_major(qx, sx, K)
+    assert np.array_equal(gs.cpu().numpy(), fs), f"{w.name}: scale bytes (whole buffer)"
+    assert np.array_equal(gq.cpu().numpy(), fq), f"{w.name}: codes (whole buffer)"
+    del gq, gs
+    S = synth.sample_rows(M, 1024 - 128, 40 + idx)
+    St = torch.from_numpy(S).cuda()
+    xs = np.ascontiguousarray(x[S])
+    oh = oracle.lowrank_down(xs, L.inv_lambda, L.L1)
+    assert rel_fro(h[St].cpu().numpy(), oh) <= 3e-5, f"{w.name}: h (row sample)"
+    y32 = svdq.linear_mxfp4(qx, sx, DL.wp, L.N, h, DL.L2, DL.bias, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    orc = oracle.linear_mxfp4(np.ascontiguousarray(fq[S]), np.ascontiguousarray(fs[S]), L.qw, L.sw, oh, L.L2, L.bias)
+    stats = check_y(host_bits(y16[St]), y32[St].cpu().numpy(), orc, w.name)
+    print(f"{w.name} mxfp4 rho={rho}: whole-buffer codes/scales ok, y ok on {len(S)} rows {stats}", flush=True)
