@@ -253,30 +253,34 @@ __global__ void pack_weight_mx_kernel(const uint8_t* __restrict__ qw, const uint
 // Stage = two 64-groups; three-slot LDS ring filled by direct global->LDS loads, protocol as in the int4
 // kernel: in the middle of stage s every wave has taken its last operand from the slot, so after the
 // barrier the slot takes stage s + 3.
-template <int MT>
+template <int MT, int WNC>
 struct MxGeom {
+    static constexpr int WAVES = 2 * WNC;                           // 2 (tokens) x WNC (channels)
     static constexpr int BM = 64 * MT;                              // tokens per block
-    static constexpr int BN = 128;                                  // channels per block
+    static constexpr int BN = 64 * WNC;                             // channels per block
     static constexpr uint32_t OFF_A = 0;                            // [group 2][half 2][BM] x 16 B
-    static constexpr uint32_t OFF_W = 64 * BM;                      // [group 2][n-block 4][64 lanes] x 16 B
-    static constexpr uint32_t OFF_SX = OFF_W + 8192;                // [BM][half 2][group 2] bytes
-    static constexpr uint32_t OFF_SW = OFF_SX + 4 * BM;             // [n-block 4][64 lanes][group 2] bytes
-    static constexpr uint32_t STAGE = OFF_SW + 512;
-    static constexpr int NDMA = MT + 2 + 1 + 1;                     // per wave and stage: MT of A, 2 of W, 1 + 1 of scales
+    static constexpr uint32_t OFF_W = 64 * BM;                      // [group 2][n-block 2 WNC][64 lanes] x 16 B
+    static constexpr uint32_t OFF_SX = OFF_W + 4096 * WNC;          // [BM][half 2][group 2] bytes
+    static constexpr uint32_t OFF_SW = OFF_SX + 4 * BM;             // [n-block 2 WNC][64 lanes][group 2] bytes
+    static constexpr uint32_t STAGE = OFF_SW + 256 * WNC;
+    // direct global->LDS loads per wave and stage.  4 waves: MT of A, 2 of W, 1 + 1 of scales;
+    // 8 waves: 2 of A, 2 of W, 1 of scales (token scales on waves 0..3, channel scales on waves 4..7)
+    static constexpr int NDMA = (WNC == 2) ? MT + 4 : 5;
+    static_assert(WNC == 2 || (WNC == 4 && MT == 4), "staging is written for 4 waves, or 8 waves with 256 tokens");
 };
 
 __device__ __forceinline__ uint32_t lds_read2(uint32_t off) {
     return *reinterpret_cast<const __attribute__((address_space(3))) uint16_t*>((lds_byte*)(uintptr_t)off);
 }
 
-template <int MT>
-__global__ __launch_bounds__(256, 2)
+template <int MT, int WNC>
+__global__ __launch_bounds__(128 * WNC, (WNC == 2) ? 2 : 1)
 void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__ sxe,
                     const uint4* __restrict__ wfrag, const uint16_t* __restrict__ wscale,
                     const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
                     int64_t M, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
                     int mtiles, int ntiles) {
-    using G = MxGeom<MT>;
+    using G = MxGeom<MT, WNC>;
     constexpr int BM = G::BM;
     constexpr int NDMA = G::NDMA;
     __shared__ __attribute__((aligned(16))) uint8_t ring[3 * G::STAGE];
@@ -301,44 +305,49 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     const int nbB = n0 >> 5;
     const uint32_t ring0 = (uint32_t)(uintptr_t)(lds_byte*)ring;
 
-    // ---- staging: wave w moves, per stage, the A chunks (group w / 2, half w % 2, 64-token quarter q = 0..MT-1),
-    // the W chunks (group w / 2, n-blocks 2 (w % 2) + {0, 1}), 64 tokens' scale bytes and one half of the
-    // channel scale bytes (waves 2, 3 repeat what waves 0, 1 move so that every wave counts NDMA loads).
-    const int cj = wave >> 1, sp = wave & 1;
-    uint32_t va[MT];
+    // ---- staging.  4 waves: wave w moves, per stage, the A chunks (group w / 2, half w % 2, 64-token quarter
+    // q = 0..MT-1), the W chunks (group w / 2, n-blocks 2 (w % 2) + {0, 1}), 64 tokens' scale bytes and one half of
+    // the channel scale bytes (waves 2, 3 repeat what waves 0, 1 move so that every wave counts NDMA loads).
+    // 8 waves: A chunks (group w / 4, half (w / 2) % 2, quarters 2 (w % 2) + {0, 1}), W chunks (group w / 4,
+    // n-blocks 2 (w % 4) + {0, 1}), and one scale transfer: tokens [64 w, +64) on waves 0..3, n-block pair w - 4 on 4..7.
+    constexpr int NA = (WNC == 2) ? MT : 2;
+    const int cj = (WNC == 2) ? (wave >> 1) : (wave >> 2);
+    const int sp = (WNC == 2) ? (wave & 1) : ((wave >> 1) & 1);
+    const int q0 = (WNC == 2) ? 0 : 2 * (wave & 1);
+    const int nb0 = (WNC == 2) ? 2 * (wave & 1) : 2 * (wave & 3);
+    uint32_t va[NA];
 #pragma unroll
-    for (int q = 0; q < MT; ++q) {
-        const int64_t row = m0 + q * 64 + lane;
+    for (int q = 0; q < NA; ++q) {
+        const int64_t row = m0 + (q0 + q) * 64 + lane;
         va[q] = (uint32_t)(((row < M) ? row : (M - 1)) * 32 + sp * 16);
     }
     const uint32_t vl16 = lane * 16;
-    const uint32_t vw[2] = {(uint32_t)((2 * sp + 0) * ng * 1024) + vl16, (uint32_t)((2 * sp + 1) * ng * 1024) + vl16};
-    uint32_t vsx = 0;                                                 // token scales: wave w moves tokens [64 w, +64) (MT = 4) ...
-    if (wave < MT) {
-        const int64_t row = m0 + wave * 64 + lane;
-        vsx = (uint32_t)(((row < M) ? row : (M - 1)) * 4);
-    } else {                                                          // ... or repeats wave w - MT's (MT = 2)
-        const int64_t row = m0 + (wave - MT) * 64 + lane;
+    const uint32_t vw[2] = {(uint32_t)((nb0 + 0) * ng * 1024) + vl16, (uint32_t)((nb0 + 1) * ng * 1024) + vl16};
+    const int sxw = (WNC == 2) ? ((wave < MT) ? wave : wave - MT) : (wave & 3);   // 64-token quarter whose scales this wave moves
+    uint32_t vsx;
+    {
+        const int64_t row = m0 + sxw * 64 + lane;
         vsx = (uint32_t)(((row < M) ? row : (M - 1)) * 4);
     }
-    const int sxw = (wave < MT) ? wave : wave - MT;
+    const int swp = (WNC == 2) ? (wave & 1) : (wave & 3);             // pair of n-blocks whose scales this wave moves
     const uint32_t vsw = (uint32_t)(kh * nstages * 128 + l32 * 4);    // channel scales: lanes 0..31 one n-block, 32..63 the next
     auto stage_issue = [&](const int s) {
         const uint32_t slot = ring0 + (uint32_t)(s % 3) * G::STAGE;
         const int g = (2 * s + cj < ng) ? 2 * s + cj : ng - 1;        // odd tail: re-read (its scale bytes are zero)
 #pragma unroll
-        for (int q = 0; q < MT; ++q)
-            dma16(qx + (size_t)g * M * 32, va[q], slot + G::OFF_A + ((cj * 2 + sp) * BM + q * 64) * 16);
+        for (int q = 0; q < NA; ++q)
+            dma16(qx + (size_t)g * M * 32, va[q], slot + G::OFF_A + ((cj * 2 + sp) * BM + (q0 + q) * 64) * 16);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-            dma16(wfrag + ((size_t)nbB * ng + g) * 64, vw[i], slot + G::OFF_W + (cj * 4 + 2 * sp + i) * 1024);
-        dma4(sxe + (size_t)s * M * 2, vsx, slot + G::OFF_SX + sxw * 256);
-        dma4(wscale + ((size_t)(nbB + 2 * sp) * nstages + s) * 64, vsw, slot + G::OFF_SW + sp * 256);
+            dma16(wfrag + ((size_t)nbB * ng + g) * 64, vw[i], slot + G::OFF_W + (cj * 2 * WNC + nb0 + i) * 1024);
+        if (WNC == 2 || wave < 4) dma4(sxe + (size_t)s * M * 2, vsx, slot + G::OFF_SX + sxw * 256);
+        if (WNC == 2 || wave >= 4)
+            dma4(wscale + ((size_t)(nbB + 2 * swp) * nstages + s) * 64, vsw, slot + G::OFF_SW + swp * 256);
     };
 
     // per-lane LDS read offsets inside a slot
     const uint32_t rd_a = G::OFF_A + (kh * BM + wm * (32 * MT) + l32) * 16;   // + group 32 BM + mi 512
-    const uint32_t rd_w = G::OFF_W + (wn * 2 * 64 + lane) * 16;               // + group 4096 + ni 1024
+    const uint32_t rd_w = G::OFF_W + (wn * 2 * 64 + lane) * 16;               // + group 2048 WNC + ni 1024
     const uint32_t rd_sx = G::OFF_SX + ((wm * (32 * MT) + l32) * 2 + kh) * 2; // + mi 128
     const uint32_t rd_sw = G::OFF_SW + (wn * 2 * 64 + lane) * 2;              // + ni 128
 
@@ -369,7 +378,7 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     auto fetch = [&](Operands& o, const uint32_t slot, const int j) {
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) {
-            o.wf[ni] = lds_read16_pinned(slot + rd_w + j * 4096 + ni * 1024);
+            o.wf[ni] = lds_read16_pinned(slot + rd_w + j * 2048 * WNC + ni * 1024);
             o.sw[ni] = lds_read2_pinned(slot + rd_sw + ni * 128);
         }
 #pragma unroll
@@ -506,9 +515,17 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
             }
     } else {
         __syncthreads();                                       // every wave is done with the operand ring
-        store_tile_bf16<MT>([&](int ni, int mi, int i) { return y[ni][mi][i]; },
-                            ring0 + wave * (32 * MT) * YROW, lane,
-                            reinterpret_cast<uint16_t*>(yout) + mw * ldy + n0 + wn * 64, ldy, M - mw);
+        uint16_t* yw = reinterpret_cast<uint16_t*>(yout) + mw * ldy + n0 + wn * 64;
+        if (WNC == 2) {
+            store_tile_bf16<MT>([&](int ni, int mi, int i) { return y[ni][mi][i]; },
+                                ring0 + wave * (32 * MT) * YROW, lane, yw, ldy, M - mw);
+        } else {                                               // eight waves: 64 tokens at a time fit the ring
+            constexpr int HM = MT / 2;
+            store_tile_bf16<HM>([&](int ni, int mi, int i) { return y[ni][mi][i]; },
+                                ring0 + wave * (32 * HM) * YROW, lane, yw, ldy, M - mw);
+            store_tile_bf16<HM>([&](int ni, int mi, int i) { return y[ni][mi + HM][i]; },
+                                ring0 + wave * (32 * HM) * YROW, lane, yw + (int64_t)(32 * HM) * ldy, ldy, M - mw - 32 * HM);
+        }
     }
 }
 
@@ -541,12 +558,21 @@ hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w
                             int64_t M, int N, int K, int r, void* y, int64_t ldy, int out_f32,
                             hipStream_t stream) {
     constexpr int MT = 4;
-    const int mtiles = (int)((M + MxGeom<MT>::BM - 1) / MxGeom<MT>::BM), ntiles = N / 128;
     const uint8_t* base = (const uint8_t*)w_packed;
-    const unsigned grid = (unsigned)(((mtiles + 63) / 64) * 64 * ntiles);
-    hipLaunchKernelGGL(gemm_mx_kernel<MT>, dim3(grid), dim3(256), 0, stream,
-                       qx, (const uint16_t*)sxe, (const uint4*)base, (const uint16_t*)(base + mx_wfrag_bytes(N, K)),
-                       h, (const uint16_t*)L2, bias, M, N, K, r, y, ldy, out_f32, mtiles, ntiles);
+    const uint16_t* wsc = (const uint16_t*)(base + mx_wfrag_bytes(N, K));
+    const int mtiles = (int)((M + 64 * MT - 1) / (64 * MT));
+    const int sms = (mtiles + 63) / 64;
+    if (N % 256 == 0) {                      // 256 x 256 block tiles, eight waves, one block per CU
+        const int ntiles = N / 256;
+        hipLaunchKernelGGL((gemm_mx_kernel<MT, 4>), dim3((unsigned)(sms * 64 * ntiles)), dim3(512), 0, stream,
+                           qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
+                           M, N, K, r, y, ldy, out_f32, mtiles, ntiles);
+    } else {                                 // 256 x 128 block tiles, four waves, two blocks per CU
+        const int ntiles = N / 128;
+        hipLaunchKernelGGL((gemm_mx_kernel<MT, 2>), dim3((unsigned)(sms * 64 * ntiles)), dim3(256), 0, stream,
+                           qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
+                           M, N, K, r, y, ldy, out_f32, mtiles, ntiles);
+    }
     return hipGetLastError();
 }
 
