@@ -331,6 +331,12 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     }
     const int swp = (WNC == 2) ? (wave & 1) : (wave & 3);             // pair of n-blocks whose scales this wave moves
     const uint32_t vsw = (uint32_t)(kh * nstages * 128 + l32 * 4);    // channel scales: lanes 0..31 one n-block, 32..63 the next
+    // eight waves: this wave's one scale transfer per stage (token scales on waves 0..3, channel scales on 4..7)
+    const uint32_t vsc = (wave < 4) ? vsx : vsw;
+    const uint8_t* sc_base = (wave < 4) ? reinterpret_cast<const uint8_t*>(sxe)
+                                        : reinterpret_cast<const uint8_t*>(wscale + (size_t)(nbB + 2 * swp) * nstages * 64);
+    const size_t sc_stride = (wave < 4) ? (size_t)M * 4 : (size_t)128;
+    const uint32_t sc_lds = (wave < 4) ? G::OFF_SX + sxw * 256 : G::OFF_SW + swp * 256;
     auto stage_issue = [&](const int s) {
         const uint32_t slot = ring0 + (uint32_t)(s % 3) * G::STAGE;
         const int g = (2 * s + cj < ng) ? 2 * s + cj : ng - 1;        // odd tail: re-read (its scale bytes are zero)
@@ -340,9 +346,15 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
 #pragma unroll
         for (int i = 0; i < 2; ++i)
             dma16(wfrag + ((size_t)nbB * ng + g) * 64, vw[i], slot + G::OFF_W + (cj * 2 * WNC + nb0 + i) * 1024);
-        if (WNC == 2 || wave < 4) dma4(sxe + (size_t)s * M * 2, vsx, slot + G::OFF_SX + sxw * 256);
-        if (WNC == 2 || wave >= 4)
+        if (WNC == 2) {
+            dma4(sxe + (size_t)s * M * 2, vsx, slot + G::OFF_SX + sxw * 256);
             dma4(wscale + ((size_t)(nbB + 2 * swp) * nstages + s) * 64, vsw, slot + G::OFF_SW + swp * 256);
+        } else {
+            // one scale transfer per wave; base, stride and destination were chosen before the loop, so there is no
+            // branch here (a branch splits the stage into basic blocks and the compiler then sinks the first
+            // group's matrix instructions past the barrier)
+            dma4(sc_base + (size_t)s * sc_stride, vsc, slot + sc_lds);
+        }
     };
 
     // per-lane LDS read offsets inside a slot
