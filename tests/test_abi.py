@@ -66,6 +66,23 @@ def test_argument_errors_before_any_launch():
     assert lib.svdq_pack_lowrank_down(a, a, 512, 24, a, z) == SHAPE
     assert lib.svdq_lowrank(2, a, 512, a, a, 4, 512, 512, 16, a, a, 512, z) == INV
     assert lib.svdq_debug_group_acc(a, a, 4, 512, 512, 2, 8, a, z) == INV     # rows beyond M
+    assert lib.svdq_debug_scale_chain(a, 1.5, 4, a, a, z) == INV
+    assert lib.svdq_debug_scale_chain(a, 0.5, 0, a, a, z) == 0
+    # MXFP4 variant: same conventions
+    qm = lib.svdq_quantize_act_mxfp4
+    assert qm(z, 512, a, 0.9, z, 4, 512, 0, a, a, z, z) == INV                # NULL x
+    assert qm(a, 512, a, 0.0, z, 4, 512, 0, a, a, z, z) == INV                # rho = 0
+    assert qm(a, 512, a, 0.9, z, 4, 512, 16, a, a, z, z) == INV               # r without packed L1
+    assert qm(a, 512, a, 0.9, z, 4, 480, 0, a, a, z, z) == SHAPE              # K % 64
+    assert qm(a, 512, a, 0.9, z, 0, 512, 0, a, a, z, z) == 0                  # M == 0 no-op
+    gm = lib.svdq_linear_mxfp4
+    assert gm(z, a, a, z, z, z, 4, 512, 512, 0, a, 512, 0, z) == INV
+    assert gm(a, a, a, a, z, z, 4, 512, 512, 16, a, 512, 0, z) == INV         # h without L2
+    assert gm(a, a, a, z, z, z, 4, 500, 512, 0, a, 512, 0, z) == SHAPE        # N % 128
+    assert gm(a, a, a, z, z, z, 0, 512, 512, 0, a, 512, 0, z) == 0
+    assert lib.svdq_pack_weight_mxfp4(z, a, 512, 512, a, z) == INV
+    assert lib.svdq_pack_weight_mxfp4(a, a, 512, 100, a, z) == SHAPE
+    assert svdq.packed_weight_mxfp4_bytes(5120, 5120) >= 5120 * 2560 and svdq.packed_weight_mxfp4_bytes(100, 5120) == 0
     assert lib.svdq_status_string(-2) == b"unsupported shape"
 
 
