@@ -185,6 +185,20 @@ int svdq_linear_mxfp4(const uint8_t* qx, const uint8_t* sx_e8m0, const void* w_p
                       void* y, int64_t ldy, int out_dtype, void* stream);
 
 /*
+ * Offline calibration, Sec. III-C: the clipping ratio of a (layer, timestep bin) is the candidate that
+ * minimises the expected squared reconstruction error || Y - Y^(rho) ||^2 of the quantised layer over
+ * the calibration steps of the bin.  The search runs the hot path (svdq_quantize_act* +
+ * svdq_linear_*) once per candidate and step and needs one more kernel, this reduction:
+ *   out[0] = sum_{m < M, n < N} (y_ref[m,n] - y[m,n])^2       (device binary64, deterministic)
+ *   y_ref_bf16 [M, ld_ref], y_bf16 [M, ldy] bf16;  N % 8 == 0, leading dimensions % 8 == 0
+ *   workspace  caller's device buffer of svdq_sq_error_workspace_bytes() bytes (partial sums)
+ * M == 0 gives 0.  The arg-min over the handful of sums is left to the caller.
+ */
+size_t svdq_sq_error_workspace_bytes(void);
+int svdq_sq_error(const void* y_ref_bf16, int64_t ld_ref, const void* y_bf16, int64_t ldy,
+                  int64_t M, int N, void* workspace, double* out, void* stream);
+
+/*
  * Test hook: the scalar part of kernel (a)'s chain, eq. 8-9, evaluated by the
  * kernel's own device functions on n given group magnitudes a[i] >= 0:
  *   s[i]   = (rho * a[i]) / 7, or 0 when that is not a normal number

@@ -219,3 +219,32 @@ def linear_mxfp4(qx, sx, qw, sw, h=None, L2_bf16=None, bias=None, want=("y64", "
         _p(out.get("ybf16"), ctypes.c_uint16), ctypes.c_int(nthreads))
     _chk(rc, "linear_mxfp4")
     return out
+
+
+# ---- clipping-ratio search (Sec. III-C) --------------------------------------------------------
+def sq_error(y_ref_bf16, y_bf16):
+    a = _c(y_ref_bf16, np.uint16)
+    b = _c(y_bf16, np.uint16)
+    assert a.shape == b.shape and a.ndim == 2
+    f = lib().svdq_oracle_sq_error
+    f.restype = ctypes.c_double
+    return float(f(_p(a, ctypes.c_uint16), _p(b, ctypes.c_uint16), ctypes.c_int64(a.shape[0]), ctypes.c_int(a.shape[1])))
+
+
+def search_clipping_ratios(layer, xs, y_refs, bins, nbins, candidates, fmt="int4"):
+    """For every timestep bin: the candidate ratio with the smallest summed squared reconstruction error of the
+    quantised layer over the bin's calibration steps.  `layer` has inv_lambda, L1, L2, qw, sw, bias (numpy);
+    xs[i] / y_refs[i] are bf16 bit arrays.  Returns (table, err [nbins][len(candidates)])."""
+    err = np.zeros((nbins, len(candidates)), np.float64)
+    for x, yr, b in zip(xs, y_refs, bins):
+        h = lowrank_down(x, layer.inv_lambda, layer.L1) if layer.r else None
+        for ci, rho in enumerate(candidates):
+            if fmt == "mxfp4":
+                qx, sx = quantize_act_mxfp4(x, layer.inv_lambda, rho)
+                y = linear_mxfp4(qx, sx, layer.qw, layer.sw, h, layer.L2 if layer.r else None, layer.bias, want=("ybf16",))
+            else:
+                qx, sx = quantize_act(x, layer.inv_lambda, rho)
+                y = linear(qx, sx, layer.qw, layer.sw, h, layer.L2 if layer.r else None, layer.bias, want=("ybf16",))
+            err[b, ci] += sq_error(yr, y["ybf16"])
+    table = [float(candidates[int(i)]) for i in err.argmin(axis=1)]
+    return table, err

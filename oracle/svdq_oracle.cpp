@@ -196,6 +196,15 @@ float svdq_oracle_alpha_lookup(const float* table, int nbins, int step, int step
     return table[bin];
 }
 
+double svdq_oracle_sq_error(const uint16_t* y_ref, const uint16_t* y, int64_t M, int N) {
+    double s = 0.0;
+    for (int64_t i = 0; i < M * (int64_t)N; ++i) {
+        double d = (double)svdq_oracle_bf16_to_f32(y_ref[i]) - (double)svdq_oracle_bf16_to_f32(y[i]);
+        s += d * d;
+    }
+    return s;
+}
+
 /* ---- MXFP4 variant ---------------------------------------------------- */
 
 static const float kE2M1[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};

@@ -103,6 +103,12 @@ int svdq_oracle_linear(const uint8_t* qx, const float* sx,
  */
 float svdq_oracle_alpha_lookup(const float* table, int nbins, int step, int step0, int nsteps_expert);
 
+/*
+ * Objective of the clipping-ratio search of Sec. III-C for one calibration step:
+ * sum_{m,n} (Y[m,n] - Y^[m,n])^2 with both outputs given as bf16 [M, N], in binary64.
+ */
+double svdq_oracle_sq_error(const uint16_t* y_ref, const uint16_t* y, int64_t M, int N);
+
 /* ------------------------------------------------------------------------
  * MXFP4 variant: the 4-bit data format the paper's tables are quoted in
  * (caption of Table I).  Same layer (eq. 5, 7, 8, 11); the uniform integer

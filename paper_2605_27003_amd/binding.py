@@ -26,6 +26,8 @@ EXPORTS = {
     "svdq_packed_weight_mxfp4_bytes": (ctypes.c_size_t, [_i32, _i32]),
     "svdq_pack_weight_mxfp4": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
     "svdq_linear_mxfp4": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _i32, _vp]),
+    "svdq_sq_error_workspace_bytes": (ctypes.c_size_t, []),
+    "svdq_sq_error": (_i32, [_vp, _i64, _vp, _i64, _i64, _i32, _vp, _vp, _vp]),
     "svdq_debug_group_acc": (_i32, [_vp, _vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp]),
     "svdq_debug_scale_chain": (_i32, [_vp, _f32, _i64, _vp, _vp, _vp]),
 }
@@ -229,6 +231,37 @@ def linear_mxfp4(qx, sx, w_packed, N, h=None, L2_bf16=None, bias=None, out=None,
     _check(load_library().svdq_linear_mxfp4(_ptr(qx), _ptr(sx), _ptr(w_packed), _ptr(h), _ptr(L2_bf16), _ptr(bias),
                                             M, N, K, r, _ptr(out), ldy, code, _stream()), "svdq_linear_mxfp4")
     return out
+
+
+# ---- clipping-ratio search (offline calibration, Sec. III-C) ---------------------------------
+def sq_error(y_ref, y, workspace=None, out=None):
+    """sum (y_ref - y)^2 over two bf16 [M,N] tensors -> 1-element float64 device tensor."""
+    M, N = y.shape
+    if workspace is None:
+        workspace = torch.empty(load_library().svdq_sq_error_workspace_bytes() // 8, dtype=torch.float64, device=y.device)
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=y.device)
+    _check(load_library().svdq_sq_error(_ptr(y_ref), y_ref.stride(0) if M > 1 else N, _ptr(y), y.stride(0) if M > 1 else N,
+                                        M, N, _ptr(workspace), _ptr(out), _stream()), "svdq_sq_error")
+    return out
+
+
+def search_clipping_ratios(layer_run, xs, y_refs, bins, nbins, candidates):
+    """Timestep-bin clipping-ratio search.  `layer_run(x, rho)` runs the quantised layer (quantise + GEMM kernels)
+    and returns y bf16; xs[i], y_refs[i] are the calibration input and full-precision output of step i, bins[i]
+    its timestep bin.  Returns (table [nbins] of chosen ratios, err [nbins][len(candidates)] summed errors)."""
+    dev = xs[0].device
+    ws = torch.empty(load_library().svdq_sq_error_workspace_bytes() // 8, dtype=torch.float64, device=dev)
+    acc = torch.zeros((nbins, len(candidates)), dtype=torch.float64, device=dev)
+    one = torch.empty(1, dtype=torch.float64, device=dev)
+    for x, yr, b in zip(xs, y_refs, bins):
+        for ci, rho in enumerate(candidates):
+            y = layer_run(x, rho)
+            sq_error(yr, y, ws, one)
+            acc[b, ci] += one[0]
+    err = acc.cpu().numpy()
+    table = [float(candidates[int(i)]) for i in err.argmin(axis=1)]
+    return table, err
 
 
 def debug_scale_chain(a, rho):

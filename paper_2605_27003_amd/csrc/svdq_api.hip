@@ -196,6 +196,18 @@ int svdq_linear_mxfp4(const uint8_t* qx, const uint8_t* sx_e8m0, const void* w_p
                                              out_dtype == SVDQ_OUT_F32, (hipStream_t)stream));
 }
 
+size_t svdq_sq_error_workspace_bytes(void) { return (size_t)svdq::SQ_ERROR_PARTIALS * sizeof(double); }
+
+int svdq_sq_error(const void* y_ref_bf16, int64_t ld_ref, const void* y_bf16, int64_t ldy,
+                  int64_t M, int N, void* workspace, double* out, void* stream) {
+    if (!y_ref_bf16 || !y_bf16 || !workspace || !out || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || N % 8 || ld_ref < N || ldy < N || ld_ref % 8 || ldy % 8) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(y_ref_bf16) || !aligned16(y_bf16) || !aligned16(workspace)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_sq_error(y_ref_bf16, ld_ref, y_bf16, ldy, M, N, (double*)workspace, out,
+                                            (hipStream_t)stream));
+}
+
 int svdq_debug_scale_chain(const float* a, float rho, int64_t n, float* s, float* inv, void* stream) {
     if (!a || !s || !inv || n < 0 || n > (int64_t)1 << 31) return SVDQ_ERR_INVALID_ARG;
     if (!(rho > 0.0f) || !(rho <= 1.0f)) return SVDQ_ERR_INVALID_ARG;

@@ -35,6 +35,11 @@ hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w
                             int64_t M, int N, int K, int r, void* y, int64_t ldy, int out_f32,
                             hipStream_t stream);
 
+// svdq_search.hip
+constexpr int SQ_ERROR_PARTIALS = 1024;
+hipError_t launch_sq_error(const void* yref, int64_t ldr, const void* y, int64_t ldy, int64_t M, int N,
+                           double* workspace, double* out, hipStream_t stream);
+
 // svdq_lowrank.hip
 hipError_t launch_lowrank_down(const void* x, int64_t ldx, const float* inv_lambda, const void* L1,
                                int64_t M, int K, int r, float* h, hipStream_t stream);
