@@ -154,6 +154,103 @@ def main():
                     ops=2.0 * M * N * K, bytes_q=M * (2 * K + K // 2 + scale_bytes + 4 * r),
                     bf16_ms=e0.elapsed_time(e1) / 20)
 
+    def measure_block(fmt):
+        """Workload with several linears (the 720p DiT block): one step = every linear's quantise pass and GEMM for the
+        expert and clipping ratios of that denoising step, walking the 40-step schedule (expert switch included)."""
+        w = synth.workload(args.workload, fmt=fmt)
+        M = w.M
+        xdev = {k: dev(v) for k, v in w.x.items()}
+        per_expert = {}
+        for ename in w.experts:
+            lins = []
+            for lin, inp in w.inputs_of.items():
+                L = w.layers[f"{ename}/{lin}"]
+                inv_lambda = dev(L.inv_lambda)
+                rec = dict(L=L, x=xdev[inp], inv_lambda=inv_lambda, L2=dev(L.L2), bias=dev(L.bias),
+                           l1p=svdq.pack_lowrank_down(dev(L.L1), inv_lambda),
+                           wp=(svdq.pack_weight if fmt == "int4" else svdq.pack_weight_mxfp4)(dev(L.qw), dev(L.sw)))
+                lins.append(rec)
+            per_expert[ename] = lins
+        bufs = {}
+        for rec in per_expert[w.experts[0]]:
+            K, N, r = rec["L"].K, rec["L"].N, rec["L"].r
+            if (K, N) not in bufs:
+                sx = (torch.empty((K // 64, M), dtype=torch.float32, device="cuda") if fmt == "int4"
+                      else torch.empty(((K // 64 + 1) // 2, M, 2, 2), dtype=torch.uint8, device="cuda"))
+                bufs[(K, N)] = (torch.empty((K // 64, M, 32), dtype=torch.uint8, device="cuda"), sx,
+                                torch.empty((M, r), dtype=torch.float32, device="cuda"),
+                                torch.empty((M, N), dtype=torch.bfloat16, device="cuda"))
+        quant = svdq.quantize_act if fmt == "int4" else svdq.quantize_act_mxfp4
+        gemm = svdq.linear_w4a4 if fmt == "int4" else svdq.linear_mxfp4
+
+        def step(i, evs=None):
+            t = i % w.nsteps
+            e = 0 if t < w.switch_step else 1
+            step0 = 0 if e == 0 else w.switch_step
+            nst = w.switch_step if e == 0 else w.nsteps - w.switch_step
+            rho = svdq.alpha_lookup(w.tables[w.experts[e]], t, step0, nst)
+            for li, rec in enumerate(per_expert[w.experts[e]]):
+                L = rec["L"]
+                qx, sx, h, y = bufs[(L.K, L.N)]
+                if evs:
+                    evs[li][0].record()
+                quant(rec["x"], rec["inv_lambda"], rho, rec["l1p"], L.r, out=(qx, sx, h))
+                if evs:
+                    evs[li][1].record()
+                gemm(qx, sx, rec["wp"], L.N, h, rec["L2"], rec["bias"], out=y)
+                if evs:
+                    evs[li][2].record()
+
+        nl = len(per_expert[w.experts[0]])
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        events = [[[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(nl)] for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i, events[i])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        tq = np.array([sum(e[0].elapsed_time(e[1]) for e in ev) for ev in events])
+        tg = np.array([sum(e[1].elapsed_time(e[2]) for e in ev) for ev in events])
+        ops = sum(2.0 * M * rec["L"].N * rec["L"].K for rec in per_expert[w.experts[0]])
+        sb = (lambda K: 4 * (K // 64)) if fmt == "int4" else (lambda K: K // 32)
+        bytes_q = sum(M * (2 * rec["L"].K + rec["L"].K // 2 + sb(rec["L"].K) + 4 * rec["L"].r) for rec in per_expert[w.experts[0]])
+        return dict(w=w, M=M, ms_step=(t1 - t0) * 1e3 / args.steps, tq=tq, tg=tg, ops=ops, bytes_q=bytes_q, nl=nl)
+
+    if args.workload == 4:
+        recs = {"int4": measure_block("int4")}
+        if not args.skip_mxfp4:
+            recs["mxfp4"] = measure_block("mxfp4")
+        B = recs["int4"]
+        gt = B["ops"] / (B["tg"].mean() * 1e-3) / 1e12
+        qg = B["bytes_q"] / (B["tq"].mean() * 1e-3) / 1e9
+        out = {
+            "metric": "W4A4 SVDQuant linear effective TOPS + % int8-MFMA peak; quantize pass GB/s",
+            "value": B["ops"] / (B["ms_step"] * 1e-3) / 1e12, "unit": "TOPS",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": B["ms_step"],
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "int4 x int4 -> int32 (int8 MFMA), fp32 dequant, bf16 out", "data": "synthetic",
+            "config": {"workload": f"{B['w'].name}: M={B['M']}, six linears (q, k, v, o 5120x5120; ffn_up 5120x13824; "
+                                   f"ffn_down 13824x5120) r=32, two experts over a 40-step schedule, ratio per timestep bin",
+                       "step": f"{B['nl']} x (svdq_quantize_act + svdq_linear_w4a4) = one DiT block-step"},
+            "roofline": {"kernel": "svdq_linear_w4a4 (gemm_kernel), six launches", "bound": "mfma", "achieved": gt,
+                         "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": gt / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                         "avg_ms": float(B["tg"].mean()), "min_ms": float(B["tg"].min())},
+            "roofline_quantize": {"kernel": "svdq_quantize_act (quantize_kernel), six launches", "bound": "hbm",
+                                  "achieved": qg, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": qg / HBM_PEAK_GBS,
+                                  "traffic": None, "algorithmic_bytes": B["bytes_q"],
+                                  "avg_ms": float(B["tq"].mean()), "min_ms": float(B["tq"].min())},
+        }
+        if "mxfp4" in recs:
+            X = recs["mxfp4"]
+            g = X["ops"] / (X["tg"].mean() * 1e-3) / 1e12
+            out["mxfp4_variant"] = {"value": X["ops"] / (X["ms_step"] * 1e-3) / 1e12, "unit": "TFLOP/s",
+                                    "ms_per_step": X["ms_step"], "gemm_TFLOPs": g, "gemm_frac_of_fp4_peak": g / FP4_MFMA_PEAK_TFLOPS,
+                                    "gemm_ms": float(X["tg"].mean()), "quantize_ms": float(X["tq"].mean())}
+        print(json.dumps(out))
+        return
+
     R = measure("int4")
     w, L, table, M, K, N, r = R["w"], R["L"], R["table"], R["M"], R["K"], R["N"], R["r"]
     ops, bytes_q, tq, tg, ms_step = R["ops"], R["bytes_q"], R["tq"], R["tg"], R["ms_step"]
