@@ -250,3 +250,56 @@ def test_scale_chain_every_mantissa(svdq, rho):
         torch.cuda.synchronize()
         assert np.array_equal(s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32)), (e, "scale")
         assert np.array_equal(inv.cpu().numpy().view(np.uint32), inv_ref.view(np.uint32)), (e, "reciprocal")
+
+
+def test_graph_capture_replays_match_eager(svdq):
+    """The library allocates nothing and never synchronises, so a step can be captured into a HIP graph.
+    Replays (with eager work and synchronisations between them) must reproduce the eager results bit for bit,
+    for both formats, on a side stream."""
+    M, K, N, r = 300, 1024, 256, 32
+    x, L = small_layer(17, M, K, N, r)
+    DL = DeviceLayer(L)
+    Lm = synth.make_layer(17, K, N, r, synth.make_x(17, M, K, outlier_count=3, outlier_scale=30.0)[1], fmt="mxfp4")
+    wpm = svdq.pack_weight_mxfp4(dev(Lm.qw), dev(Lm.sw))
+    xt = [dev(x), dev(np.roll(x, 5, axis=0))]
+    qx = torch.empty((K // 64, M, 32), dtype=torch.uint8, device="cuda")
+    sx = torch.empty((K // 64, M), dtype=torch.float32, device="cuda")
+    sxm = torch.empty(((K // 64 + 1) // 2, M, 2, 2), dtype=torch.uint8, device="cuda")
+    h = torch.empty((M, r), dtype=torch.float32, device="cuda")
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    ym = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    xin = torch.empty_like(xt[0])
+
+    def step():
+        svdq.quantize_act(xin, DL.inv_lambda, 0.8, DL.l1p, r, out=(qx, sx, h))
+        svdq.linear_w4a4(qx, sx, DL.wp, N, h, DL.L2, DL.bias, out=y)
+        svdq.quantize_act_mxfp4(xin, DL.inv_lambda, 0.8, DL.l1p, r, out=(qx, sxm, h))
+        svdq.linear_mxfp4(qx, sxm, wpm, N, h, DL.L2, DL.bias, out=ym)
+
+    eager = []
+    for xv in xt:
+        xin.copy_(xv)
+        step()
+        torch.cuda.synchronize()
+        eager.append((y.clone(), ym.clone()))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        xin.copy_(xt[0])
+        step()                                              # warm-up on the capture stream
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        xin.copy_(xt[rep % 2])
+        y.zero_()
+        ym.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, eager[rep % 2][0]) and torch.equal(ym, eager[rep % 2][1]), rep
+        xin.copy_(xt[(rep + 1) % 2])                        # eager work between the replays
+        step()
+        torch.cuda.synchronize()
