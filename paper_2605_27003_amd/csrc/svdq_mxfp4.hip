@@ -266,6 +266,7 @@ struct MxGeom {
     // direct global->LDS loads per wave and stage.  4 waves: MT of A, 2 of W, 1 + 1 of scales;
     // 8 waves: 2 of A, 2 of W, 1 of scales (token scales on waves 0..3, channel scales on waves 4..7)
     static constexpr int NDMA = (WNC == 2) ? MT + 4 : 5;
+    static constexpr int NS = (WNC == 2) ? 3 : 4;                   // LDS ring slots: 78 KB (two blocks per CU) or 136 KB (one)
     static_assert(WNC == 2 || (WNC == 4 && MT == 4), "staging is written for 4 waves, or 8 waves with 256 tokens");
 };
 
@@ -283,7 +284,8 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     using G = MxGeom<MT, WNC>;
     constexpr int BM = G::BM;
     constexpr int NDMA = G::NDMA;
-    __shared__ __attribute__((aligned(16))) uint8_t ring[3 * G::STAGE];
+    constexpr int NS = G::NS;
+    __shared__ __attribute__((aligned(16))) uint8_t ring[NS * G::STAGE];
 
     // XCD-aware tile order (consecutive block ids go round-robin to the 8 XCDs): each XCD walks its own
     // token tiles, 8 at a time across n.
@@ -338,7 +340,7 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     const size_t sc_stride = (wave < 4) ? (size_t)M * 4 : (size_t)128;
     const uint32_t sc_lds = (wave < 4) ? G::OFF_SX + sxw * 256 : G::OFF_SW + swp * 256;
     auto stage_issue = [&](const int s) {
-        const uint32_t slot = ring0 + (uint32_t)(s % 3) * G::STAGE;
+        const uint32_t slot = ring0 + (uint32_t)(s % NS) * G::STAGE;
         const int g = (2 * s + cj < ng) ? 2 * s + cj : ng - 1;        // odd tail: re-read (its scale bytes are zero)
 #pragma unroll
         for (int q = 0; q < NA; ++q)
@@ -371,12 +373,18 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
 #pragma unroll
             for (int i = 0; i < 16; ++i) y[a][b][i] = 0.0f;
 
-    stage_issue(0);
-    if (nstages > 1) stage_issue(1);
-    if (nstages > 2) stage_issue(2);
-    if (nstages > 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
-    else if (nstages > 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // wait until at most k stages' worth of this wave's transfers are outstanding (k = 0 .. NS - 1)
+    auto wait_stages = [&](const int k) {
+        if (k <= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (k == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
+        else if (k == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * NDMA) : "memory");
+    };
+    {
+        const int pre = nstages < NS ? nstages : NS;
+        for (int s = 0; s < pre; ++s) stage_issue(s);
+        wait_stages(pre - 1);
+    }
     __syncthreads();
 
     // Two operand register sets: set 0 feeds the first group of a stage (scale byte 0 of each 16-bit scale
@@ -412,7 +420,7 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
         }
     };
 
-    // One stage.  FULL: stages s+1..s+3 exist, so the body is straight-line code (the compiler otherwise sinks
+    // One stage.  FULL: stages s+1..s+NS exist, so the body is straight-line code (the compiler otherwise sinks
     // the first group's matrix instructions past the conditional blocks, next to the second group's).
     auto stage_body = [&](const int s, const uint32_t cur, const uint32_t nxt, auto FULLC) {
         constexpr bool FULL = decltype(FULLC)::value;
@@ -422,13 +430,13 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
         mma_group(op0, IC<0>{});
         __builtin_amdgcn_sched_barrier(0);
         // This wave has now requested everything it needs from the slot (the barrier waits for the loads to
-        // return), so after the barrier the slot can take stage s + 3; stage s + 1, requested two stages ago, is
-        // made visible for the fetch below.
+        // return), so after the barrier the slot can take stage s + NS; stage s + 1, requested NS - 1 stages ago,
+        // is made visible for the fetch below (stages s + 2 .. s + NS - 1 may stay in flight).
         if (FULL || s + 1 < nstages) {
-            if (FULL || s + 2 < nstages) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (FULL) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NDMA) : "memory");
+            else wait_stages((nstages - 1 < s + NS - 1 ? nstages - 1 : s + NS - 1) - (s + 1));
             __syncthreads();
-            if (FULL || s + 3 < nstages) stage_issue(s + 3);
+            if (FULL || s + NS < nstages) stage_issue(s + NS);
             fetch(op0, nxt, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -437,9 +445,9 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     };
     fetch(op0, ring0, 0);
     uint32_t cur = ring0;
-    auto next_slot = [&](const uint32_t c) { return (c == ring0 + 2 * G::STAGE) ? ring0 : c + G::STAGE; };
+    auto next_slot = [&](const uint32_t c) { return (c == ring0 + (NS - 1) * G::STAGE) ? ring0 : c + G::STAGE; };
     int s = 0;
-    for (; s + 3 < nstages; ++s) {
+    for (; s + NS < nstages; ++s) {
         const uint32_t nxt = next_slot(cur);
         stage_body(s, cur, nxt, IC<1>{});
         cur = nxt;
