@@ -96,6 +96,24 @@ def test_ragged_shapes(svdq, oracle, M, K, N, r):
     check_y(host_bits(y16), y32.cpu().numpy(), orc, f"M{M} K{K} N{N} r{r}")
 
 
+def test_maximum_k(svdq, oracle):
+    """K at the library's limit (the smoothing vector fills the 64 KB of dynamic LDS), both formats."""
+    M, K, N, r = 70, 16384, 128, 16
+    x, L = small_layer(19, M, K, N, r, outliers=5)
+    DL = DeviceLayer(L)
+    qx, sx, h = run_quant(svdq, x, DL, 0.9)
+    oq, os_, oh = check_quant(oracle, x, L, 0.9, qx, sx, h, "max K")
+    y = svdq.linear_w4a4(qx, sx, DL.wp, N, h, DL.L2, DL.bias)
+    y32 = svdq.linear_w4a4(qx, sx, DL.wp, N, h, DL.L2, DL.bias, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check_y(host_bits(y), y32.cpu().numpy(), oracle.linear(oq, os_, L.qw, L.sw, oh, L.L2, L.bias), "max K")
+    qm, sm, hm = svdq.quantize_act_mxfp4(dev(x), DL.inv_lambda, 0.9, DL.l1p, r)
+    torch.cuda.synchronize()
+    omq, oms = oracle.quantize_act_mxfp4(x, L.inv_lambda, 0.9)
+    gq, gs = svdq.mx_to_token_major(qm, sm, K)
+    assert np.array_equal(gq.cpu().numpy(), omq) and np.array_equal(gs.cpu().numpy(), oms)
+
+
 def test_strided_input_and_output(svdq, oracle):
     M, K, N, r = 77, 512, 256, 16
     x, L = small_layer(3, M, K, N, r)
