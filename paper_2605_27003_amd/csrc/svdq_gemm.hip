@@ -23,15 +23,23 @@
 //    true partial sum.
 //
 // Orientation: the MFMA computes the transposed tile D[n][m] (weights are the A
-// operand).  Everything the matrix cores consume reaches them through LDS, staged
-// one stage (two groups) ahead, so the compute path has no global-memory waits.
-// Staging uses the direct global->LDS loads of gfx950 (global_load_lds_dwordx4):
-// no registers, no VALU work and no ds_write for the bulk data.  Codes of both
-// operands stay 4-bit in LDS and are unpacked in registers by the wave that
-// multiplies them; weight fragments, the bf16 pieces of the weight scales and the
-// correction operands are prepacked offline in fragment order; activations arrive
-// group-major from the quantise kernel, which is fragment order already.
-// Block tile 128 x 128, 4 waves of 64 x 64.
+// operand).  Everything the matrix cores consume reaches them through LDS: a
+// three-slot ring of stages (two groups each) filled by the direct global->LDS
+// loads of gfx950 (global_load_lds_dwordx4 / _dword: no registers, no VALU work,
+// no ds_write), requested up to three stages ahead, so the compute path has no
+// global-memory waits.  Codes of both operands stay 4-bit in LDS and are unpacked
+// in registers by the wave that multiplies them; weight fragments, the bf16 pieces
+// of the weight scales and the correction operands are prepacked offline in
+// fragment order; activations arrive group-major from the quantise kernel, which
+// is fragment order already.  Block tile 128 x 128, 4 waves of 64 x 64.
+//
+// The K loop is a software pipeline over 32 x 32 tiles: a step issues the matrix
+// instructions of tile t, then the vector ALU folds tile t-1 (results that
+// completed a step ago) and unpacks operands; LDS operands are requested one
+// group ahead.  The kernel is bound by vector-ALU issue (16 FMAs + 12 unpack
+// operations per tile and group against 114 clocks of matrix pipe), not by the
+// matrix cores.  The output tile leaves through an LDS transpose as full
+// 128-byte lines.
 #include "svdq_dev.h"
 #include "svdq_kernels.h"
 #include "svdq_lds.h"
