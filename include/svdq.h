@@ -156,6 +156,52 @@ int svdq_debug_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int
                          int64_t m0, int mt, int32_t* acc, void* stream);
 
 /*
+ * ---- E3M2-container execution of the same int4 layer (eq. 3, 5, 7, 8, 11): identical codes,
+ * scales and arithmetic (one exact integer sum per 64-group, binary32 dequantisation), with each
+ * 4-bit code q in [-8, 7] stored as the 6-bit floating-point field that equals q (1 sign bit,
+ * 3 exponent bits of bias 3, 2 mantissa bits: 0 -> 0, +-1 -> 12, +-2 -> 16, +-3 -> 18, +-4..7 -> 20..23,
+ * -8 -> 56; sign in bit 5).  gfx950 has no int4 matrix instruction; its FP6 matrix instruction
+ * multiplies these fields exactly, a whole group per instruction, at twice the int8 rate and
+ * without unpacking, so this is the fast way to run the layer on this chip.  It costs 6 bits per
+ * code in memory instead of 4.  The canonical weight input is the same as for svdq_pack_weight.
+ *
+ * Activation operand buffer `act`, svdq_act_e3m2_bytes(M, K) bytes, device: for each 64-group g a
+ * block of Mp = round_up(M, 4) rows, 52 bytes per row, in three planes
+ *     [Mp][2][16 B]   bytes 0..15 of the 24 code bytes of (row, 32-k half); fields ascend from bit 0
+ *     [2][Mp][8 B]    bytes 16..23
+ *     [Mp][4 B]       token scale s[m,g] as two bf16 pieces, hi | lo << 16 (hi + lo ~ s, 16 bits)
+ * Rows M..Mp-1 are padding: never written, read only into results that are discarded.
+ */
+size_t svdq_act_e3m2_bytes(int64_t M, int K);
+
+/* Kernel (a) writing `act`.  Arguments as svdq_quantize_act; sx [K/64][M] binary32 (the exact
+ * scales, for inspection) may be NULL.  Codes and scales are bit-identical to svdq_quantize_act. */
+int svdq_quantize_act_e3m2(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                           const void* l1_packed, int64_t M, int K, int r,
+                           uint8_t* act, float* sx, float* h, void* stream);
+
+/* act -> nibble codes qx [K/64][M][32 B] in the layout of svdq_quantize_act (format conversion
+ * and test hook). */
+int svdq_unpack_act_e3m2(const uint8_t* act, int64_t M, int K, uint8_t* qx, void* stream);
+
+/* Offline weight packing for svdq_linear_w4a4_e3m2: qw [N, K/2] nibbles and sw [K/64, N] binary32
+ * as for svdq_pack_weight; w_packed out, svdq_packed_weight_e3m2_bytes(N, K) bytes (0 for
+ * unsupported shapes), 16-byte aligned. */
+size_t svdq_packed_weight_e3m2_bytes(int N, int K);
+int svdq_pack_weight_e3m2(const uint8_t* qw, const float* sw, int N, int K, void* w_packed, void* stream);
+
+/* Kernels (b)+(c) on `act`: y as svdq_linear_w4a4 (same shapes, constraints and error behaviour). */
+int svdq_linear_w4a4_e3m2(const uint8_t* act, const void* w_packed,
+                          const float* h, const void* L2_bf16, const float* bias,
+                          int64_t M, int N, int K, int r,
+                          void* y, int64_t ldy, int out_dtype, void* stream);
+
+/* Test hook: the integer group sums as the FP6 matrix-core path forms them; acc out [mt, N, K/64]
+ * int32, rows [m0, m0 + mt) as for svdq_debug_group_acc. */
+int svdq_debug_group_acc_e3m2(const uint8_t* act, const void* w_packed, int64_t M, int N, int K,
+                              int64_t m0, int mt, int32_t* acc, void* stream);
+
+/*
  * ---- MXFP4 variant: the 4-bit data format of the paper's Table I on the block-scaled
  * matrix instruction of gfx950.  Same layer (eq. 5, 7, 8, 11) and same calling conventions;
  * the integer grid of eq. 3 is replaced by microscaling FP4: blocks of 32 values along K share

@@ -1,4 +1,5 @@
 """ctypes binding of include/svdq.h for torch tensors (device memory and streams only)."""
+import collections
 import ctypes
 import os
 
@@ -22,6 +23,13 @@ EXPORTS = {
     "svdq_pack_weight": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
     "svdq_linear_w4a4": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _i32, _vp]),
     "svdq_lowrank": (_i32, [_i32, _vp, _i64, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _i64, _vp]),
+    "svdq_act_e3m2_bytes": (ctypes.c_size_t, [_i64, _i32]),
+    "svdq_quantize_act_e3m2": (_i32, [_vp, _i64, _vp, _f32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "svdq_unpack_act_e3m2": (_i32, [_vp, _i64, _i32, _vp, _vp]),
+    "svdq_packed_weight_e3m2_bytes": (ctypes.c_size_t, [_i32, _i32]),
+    "svdq_pack_weight_e3m2": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
+    "svdq_linear_w4a4_e3m2": (_i32, [_vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _i32, _vp]),
+    "svdq_debug_group_acc_e3m2": (_i32, [_vp, _vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp]),
     "svdq_quantize_act_mxfp4": (_i32, [_vp, _i64, _vp, _f32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
     "svdq_packed_weight_mxfp4_bytes": (ctypes.c_size_t, [_i32, _i32]),
     "svdq_pack_weight_mxfp4": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
@@ -180,6 +188,76 @@ def debug_group_acc(qx, w_packed, N, m0, mt):
     return acc
 
 
+# ---- E3M2-container execution of the int4 layer -------------------------------------------------
+class ActE3M2(collections.namedtuple("ActE3M2", "buf M K")):
+    """Activation operand buffer of the FP6 matrix-core path (layout in include/svdq.h) with its logical shape."""
+
+
+def act_e3m2_bytes(M, K):
+    return load_library().svdq_act_e3m2_bytes(M, K)
+
+
+def quantize_act_e3m2(x_bf16, inv_lambda, rho, l1_packed=None, r=0, out=None, want_sx=True):
+    """x [M,K] bf16 -> (act ActE3M2, sx [K/64,M] f32 or None, h [M,r] f32 or None).  Same codes and scales as
+    quantize_act, codes held as E3M2 fields."""
+    M, K = x_bf16.shape
+    assert x_bf16.dtype == torch.bfloat16 and x_bf16.stride(1) == 1
+    dev = x_bf16.device
+    if out is None:
+        act = ActE3M2(torch.empty(act_e3m2_bytes(M, K), dtype=torch.uint8, device=dev), M, K)
+        sx = torch.empty((K // 64, M), dtype=torch.float32, device=dev) if want_sx else None
+        h = torch.empty((M, r), dtype=torch.float32, device=dev) if l1_packed is not None else None
+    else:
+        act, sx, h = out
+        assert act.M == M and act.K == K
+    ldx = x_bf16.stride(0) if M > 1 else K
+    _check(load_library().svdq_quantize_act_e3m2(_ptr(x_bf16), ldx, _ptr(inv_lambda), float(rho), _ptr(l1_packed),
+                                                M, K, r if l1_packed is not None else 0,
+                                                _ptr(act.buf), _ptr(sx), _ptr(h), _stream()), "svdq_quantize_act_e3m2")
+    return act, sx, h
+
+
+def unpack_act_e3m2(act):
+    """ActE3M2 -> nibble codes qx [K/64,M,32] u8 in the layout of quantize_act."""
+    qx = torch.empty((act.K // 64, act.M, 32), dtype=torch.uint8, device=act.buf.device)
+    _check(load_library().svdq_unpack_act_e3m2(_ptr(act.buf), act.M, act.K, _ptr(qx), _stream()), "svdq_unpack_act_e3m2")
+    return qx
+
+
+def packed_weight_e3m2_bytes(N, K):
+    return load_library().svdq_packed_weight_e3m2_bytes(N, K)
+
+
+def pack_weight_e3m2(qw, sw):
+    """qw [N,K/2] uint8 canonical codes, sw [K/64,N] f32 (device) -> opaque uint8 tensor for linear_w4a4_e3m2."""
+    N, K2 = qw.shape
+    K = 2 * K2
+    out = torch.empty(packed_weight_e3m2_bytes(N, K), dtype=torch.uint8, device=qw.device)
+    _check(load_library().svdq_pack_weight_e3m2(_ptr(qw), _ptr(sw), N, K, _ptr(out), _stream()), "svdq_pack_weight_e3m2")
+    return out
+
+
+def linear_w4a4_e3m2(act, w_packed, N, h=None, L2_bf16=None, bias=None, out=None, out_dtype=torch.bfloat16):
+    """ActE3M2 -> y [M,N] bf16 (or f32: the value before the bf16 rounding)."""
+    M, K = act.M, act.K
+    r = 0 if h is None else h.shape[1]
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=act.buf.device)
+    code = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
+    ldy = out.stride(0) if M > 1 else N
+    _check(load_library().svdq_linear_w4a4_e3m2(_ptr(act.buf), _ptr(w_packed), _ptr(h), _ptr(L2_bf16), _ptr(bias),
+                                               M, N, K, r, _ptr(out), ldy, code, _stream()), "svdq_linear_w4a4_e3m2")
+    return out
+
+
+def debug_group_acc_e3m2(act, w_packed, N, m0, mt):
+    """Integer group sums of rows [m0, m0+mt) as the FP6 matrix-core path forms them -> [mt, N, K/64] int32."""
+    acc = torch.empty((mt, N, act.K // 64), dtype=torch.int32, device=act.buf.device)
+    _check(load_library().svdq_debug_group_acc_e3m2(_ptr(act.buf), _ptr(w_packed), act.M, N, act.K, m0, mt,
+                                                   _ptr(acc), _stream()), "svdq_debug_group_acc_e3m2")
+    return acc
+
+
 # ---- MXFP4 variant ---------------------------------------------------------------------------
 def quantize_act_mxfp4(x_bf16, inv_lambda, rho, l1_packed=None, r=0, out=None):
     """x [M,K] bf16 -> (qx [K/64,M,32] u8 E2M1 codes, sx [ceil(K/128),M,2,2] u8 E8M0 bytes, h [M,r] f32 or None)."""
@@ -275,22 +353,30 @@ def debug_scale_chain(a, rho):
 
 
 class W4A4Linear:
-    """One quantised linear resident in HBM: packed weights and low-rank factors, reusable output buffers."""
+    """One quantised linear resident in HBM: packed weights and low-rank factors, reusable output buffers.
 
-    def __init__(self, inv_lambda, L1_bf16, L2_bf16, qw, sw, bias):
+    container "e3m2" (default) runs the FP6 matrix-core path, "nibble" the int8 one on 4-bit storage."""
+
+    def __init__(self, inv_lambda, L1_bf16, L2_bf16, qw, sw, bias, container="e3m2"):
+        assert container in ("e3m2", "nibble")
+        self.container = container
         self.N, self.K = qw.shape[0], qw.shape[1] * 2
         self.r = 0 if L1_bf16 is None else L1_bf16.shape[1]
         self.inv_lambda = inv_lambda
         self.l1_packed = pack_lowrank_down(L1_bf16, inv_lambda) if self.r else None
         self.L2 = L2_bf16 if self.r else None
-        self.w_packed = pack_weight(qw, sw)
+        self.w_packed = pack_weight_e3m2(qw, sw) if container == "e3m2" else pack_weight(qw, sw)
         self.bias = bias
         self._bufs = None
 
     def buffers(self, M, device):
-        if self._bufs is None or self._bufs[0].shape[0] != M:
-            qx = torch.empty((self.K // 64, M, 32), dtype=torch.uint8, device=device)
-            sx = torch.empty((self.K // 64, M), dtype=torch.float32, device=device)
+        if self._bufs is None or self._bufs[3].shape[0] != M:
+            if self.container == "e3m2":
+                qx = ActE3M2(torch.empty(act_e3m2_bytes(M, self.K), dtype=torch.uint8, device=device), M, self.K)
+                sx = None
+            else:
+                qx = torch.empty((self.K // 64, M, 32), dtype=torch.uint8, device=device)
+                sx = torch.empty((self.K // 64, M), dtype=torch.float32, device=device)
             h = torch.empty((M, self.r), dtype=torch.float32, device=device) if self.r else None
             y = torch.empty((M, self.N), dtype=torch.bfloat16, device=device)
             self._bufs = (qx, sx, h, y)
@@ -298,9 +384,14 @@ class W4A4Linear:
 
     def quantize(self, x_bf16, rho):
         qx, sx, h, _ = self.buffers(x_bf16.shape[0], x_bf16.device)
+        if self.container == "e3m2":
+            return quantize_act_e3m2(x_bf16, self.inv_lambda, rho, self.l1_packed, self.r, out=(qx, sx, h))
         return quantize_act(x_bf16, self.inv_lambda, rho, self.l1_packed, self.r, out=(qx, sx, h))
 
     def gemm(self, qx, sx, h):
+        if self.container == "e3m2":
+            y = self.buffers(qx.M, qx.buf.device)[3]
+            return linear_w4a4_e3m2(qx, self.w_packed, self.N, h, self.L2, self.bias, out=y)
         y = self.buffers(qx.shape[1], qx.device)[3]
         return linear_w4a4(qx, sx, self.w_packed, self.N, h, self.L2, self.bias, out=y)
 

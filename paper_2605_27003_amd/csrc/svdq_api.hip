@@ -147,6 +147,79 @@ int svdq_debug_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int
     return hip_status(svdq::launch_group_acc(qx, w_packed, M, N, K, m0, mt, acc, (hipStream_t)stream));
 }
 
+size_t svdq_act_e3m2_bytes(int64_t M, int K) {
+    if (M < 0 || K <= 0 || K % SVDQ_GROUP) return 0;
+    return svdq::act_e3m2_bytes(M, K);
+}
+
+int svdq_quantize_act_e3m2(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                           const void* l1_packed, int64_t M, int K, int r,
+                           uint8_t* act, float* sx, float* h, void* stream) {
+    if (!x_bf16 || !inv_lambda || !act || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (!(rho > 0.0f) || !(rho <= 1.0f)) return SVDQ_ERR_INVALID_ARG;      // also rejects NaN
+    if (l1_packed ? (!h) : (r != 0)) return SVDQ_ERR_INVALID_ARG;
+    if (K <= 0 || K % SVDQ_GROUP || K > SVDQ_MAX_K || ldx < K || ldx % 8) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (l1_packed && !rank_ok(r)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(x_bf16) || !aligned16(inv_lambda) || !aligned16(act) || !aligned16(sx) ||
+        !aligned16(l1_packed) || (l1_packed && !aligned16(h)))
+        return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_quantize_e3m2(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, act, sx, h,
+                                                 (hipStream_t)stream));
+}
+
+int svdq_unpack_act_e3m2(const uint8_t* act, int64_t M, int K, uint8_t* qx, void* stream) {
+    if (!act || !qx || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (K <= 0 || K % SVDQ_GROUP) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(act) || !aligned16(qx)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_unpack_act_e3m2(act, M, K, qx, (hipStream_t)stream));
+}
+
+size_t svdq_packed_weight_e3m2_bytes(int N, int K) {
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE) return 0;
+    return svdq::packed_weight_e3m2_bytes(N, K);
+}
+
+int svdq_pack_weight_e3m2(const uint8_t* qw, const float* sw, int N, int K, void* w_packed, void* stream) {
+    if (!qw || !sw || !w_packed) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(qw) || !aligned16(sw) || !aligned16(w_packed)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_pack_weight_e3m2(qw, sw, N, K, w_packed, (hipStream_t)stream));
+}
+
+int svdq_linear_w4a4_e3m2(const uint8_t* act, const void* w_packed,
+                          const float* h, const void* L2_bf16, const float* bias,
+                          int64_t M, int N, int K, int r,
+                          void* y, int64_t ldy, int out_dtype, void* stream) {
+    if (!act || !w_packed || !y || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (out_dtype != SVDQ_OUT_BF16 && out_dtype != SVDQ_OUT_F32) return SVDQ_ERR_INVALID_ARG;
+    if (r == 0 ? (h || L2_bf16) : (!h || !L2_bf16)) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE || ldy < N || ldy % 8)
+        return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (r != 0 && !rank_ok(r)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(act) || !aligned16(w_packed) || !aligned16(h) || !aligned16(L2_bf16) ||
+        !aligned16(bias) || !aligned16(y))
+        return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_linear_e3m2(act, w_packed, h, L2_bf16, bias, M, N, K, r, y, ldy,
+                                               out_dtype == SVDQ_OUT_F32, (hipStream_t)stream));
+}
+
+int svdq_debug_group_acc_e3m2(const uint8_t* act, const void* w_packed, int64_t M, int N, int K,
+                              int64_t m0, int mt, int32_t* acc, void* stream) {
+    if (!act || !w_packed || !acc || M < 0 || m0 < 0 || mt < 0 || m0 + mt > M) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(act) || !aligned16(w_packed)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (mt == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_group_acc_e3m2(act, w_packed, M, N, K, m0, mt, acc, (hipStream_t)stream));
+}
+
 int svdq_quantize_act_mxfp4(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
                             const void* l1_packed, int64_t M, int K, int r,
                             uint8_t* qx, uint8_t* sx_e8m0, float* h, void* stream) {

@@ -24,6 +24,23 @@ hipError_t launch_linear(const uint8_t* qx, const float* sx, const void* w_packe
 hipError_t launch_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int N, int K,
                             int64_t m0, int mt, int32_t* acc, hipStream_t stream);
 
+// E3M2-container variant of the int4 path (svdq_quantize.hip, svdq_gemm_e3m2.hip).  The activation operand
+// buffer holds, per 64-group, Mp = round_up(M, 4) rows of 52 bytes in three planes (see quantize_kernel).
+constexpr int E3M2_ROW_BYTES = 52;
+inline size_t act_e3m2_bytes(int64_t M, int K) { return (size_t)(K / 64) * (size_t)((M + 3) & ~(int64_t)3) * E3M2_ROW_BYTES; }
+hipError_t launch_quantize_e3m2(const void* x, int64_t ldx, const float* inv_lambda, float rho,
+                                const void* l1p, int64_t M, int K, int r,
+                                uint8_t* act, float* sx, float* h, hipStream_t stream);
+size_t packed_weight_e3m2_bytes(int N, int K);
+hipError_t launch_pack_weight_e3m2(const uint8_t* qw, const float* sw, int N, int K, void* out, hipStream_t stream);
+hipError_t launch_linear_e3m2(const uint8_t* act, const void* w_packed,
+                              const float* h, const void* L2, const float* bias,
+                              int64_t M, int N, int K, int r, void* y, int64_t ldy, int out_f32,
+                              hipStream_t stream);
+hipError_t launch_group_acc_e3m2(const uint8_t* act, const void* w_packed, int64_t M, int N, int K,
+                                 int64_t m0, int mt, int32_t* acc, hipStream_t stream);
+hipError_t launch_unpack_act_e3m2(const uint8_t* act, int64_t M, int K, uint8_t* qx, hipStream_t stream);
+
 // svdq_mxfp4.hip
 size_t packed_weight_mx_bytes(int N, int K);
 hipError_t launch_pack_weight_mx(const uint8_t* qw, const uint8_t* sw, int N, int K, void* out, hipStream_t stream);

@@ -19,6 +19,7 @@
 // binary32 on the vector ALU.
 #include "svdq_dev.h"
 #include "svdq_kernels.h"
+#include "svdq_lds.h"
 
 namespace svdq {
 
@@ -62,9 +63,18 @@ constexpr uint32_t RNE_MAGIC_BITS = 0x4B400008u;            // 1.5*2^23 + 8: rou
 // results are folded with w = (w << 4) + t
 constexpr uint32_t PACK_JUNK = (uint32_t)(0x4B400000ull * 0x11111111ull);
 
+// Codes of one lane: 32 consecutive k of one token row.  Nibbles: 16 bytes, two's complement, k ascending from
+// the low nibble of byte 0.  E3M2: the same integers as 6-bit floating-point fields (sign, 3 exponent bits of
+// bias 3, 2 mantissa bits; every integer in [-8, 8] is exact there), 24 bytes, k ascending from bit 0: the
+// operand format of the FP6 matrix instructions, which run at twice the int8 rate.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
+template <bool E3M2> struct LaneCodes { uint4 lo; uint2 hi; };
+
 // One 32-row block of one group: quantiser chain on this lane's 32 values.
+template <bool E3M2>
 __device__ __forceinline__ void quantize_rows(const uint4 (&xv)[4], const float* __restrict__ il_lds, float rho,
-                                              uint4& codes, float& s_out) {
+                                              LaneCodes<E3M2>& codes, float& s_out) {
     float xs[32];
     float a = 0.0f;
 #pragma unroll
@@ -95,6 +105,23 @@ __device__ __forceinline__ void quantize_rows(const uint4 (&xv)[4], const float*
     // 1.5*2^23 + 8 rounds to nearest-even and leaves code + 8 (0..15) in the low mantissa bits, so eight
     // results fold into a dword with shift-adds and no carries between nibbles; the folded exponent
     // bits are a constant, and x ^ 8 turns a biased nibble back into two's complement.
+    if constexpr (E3M2) {
+        // same decision (clamp, then round to nearest even integer), then the hardware conversion of the 32
+        // integer-valued floats to E3M2 fields, which is exact on them.  It interleaves its two inputs:
+        // field 2 j comes from the first vector, field 2 j + 1 from the second.
+        f32x16 ev, od;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float u0 = __builtin_amdgcn_fmed3f(__fmul_rn(xs[2 * j], inv), -8.0f, 7.0f);
+            const float u1 = __builtin_amdgcn_fmed3f(__fmul_rn(xs[2 * j + 1], inv), -8.0f, 7.0f);
+            ev[j] = __builtin_rintf(u0);
+            od[j] = __builtin_rintf(u1);
+        }
+        const u32x6 c = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(ev, od, 1.0f);
+        codes.lo = uint4{c[0], c[1], c[2], c[3]};
+        codes.hi = uint2{c[4], c[5]};
+        return;
+    }
     uint32_t packed[4];
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
@@ -108,12 +135,18 @@ __device__ __forceinline__ void quantize_rows(const uint4 (&xv)[4], const float*
         }
         packed[d] = (wd - PACK_JUNK) ^ 0x88888888u;
     }
-    codes = uint4{packed[0], packed[1], packed[2], packed[3]};
+    codes.lo = uint4{packed[0], packed[1], packed[2], packed[3]};
 }
 
 constexpr int HPART_BYTES = WAVES * ROWS_PER_BLOCK * 33 * 4;
 
-template <bool LOWRANK>
+// E3M2 = false: qx [K/64][M][32 B] nibbles.  E3M2 = true: qx is the activation operand buffer of the FP6 GEMM,
+// per group a block of Mp rows (Mp = M rounded up to a multiple of 4; rows M..Mp-1 are never written):
+//   [Mp][2 halves][16 B]   bytes 0..15 of each lane's 24 code bytes
+//   [2 halves][Mp][8 B]    bytes 16..23
+//   [Mp] x 4 B             the token scale as two bf16 pieces (hi | lo << 16), the scale-product MFMA operand
+// sx [K/64][M] binary32 is written in both cases (skipped if null with E3M2).
+template <bool LOWRANK, bool E3M2>
 __global__ __launch_bounds__(256, 2)
 void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
                      const float* __restrict__ inv_lambda, float rho,
@@ -190,13 +223,24 @@ void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
             const float* il_lds = il_s + g * 64 + hf * 32;
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
-                uint4 codes;
+                LaneCodes<E3M2> codes;
                 float s;
-                quantize_rows(xc[b], il_lds, rho, codes, s);
+                quantize_rows<E3M2>(xc[b], il_lds, rho, codes, s);
                 // group-major outputs: the 32 rows of this block are 1 KB of codes and 128 B of scales, contiguous
                 if (rows[b] < M) {
-                    *reinterpret_cast<uint4*>(qx + ((size_t)g * M + rows[b]) * 32 + hf * 16) = codes;
-                    if (hf == 0) sx[(size_t)g * M + rows[b]] = s;
+                    if constexpr (E3M2) {
+                        const size_t Mp = (size_t)((M + 3) & ~(int64_t)3);
+                        uint8_t* blk = qx + (size_t)g * Mp * E3M2_ROW_BYTES;
+                        *reinterpret_cast<uint4*>(blk + (size_t)rows[b] * 32 + hf * 16) = codes.lo;
+                        *reinterpret_cast<uint2*>(blk + Mp * 32 + ((size_t)hf * Mp + rows[b]) * 8) = codes.hi;
+                        if (hf == 0) {
+                            *reinterpret_cast<uint32_t*>(blk + Mp * 48 + (size_t)rows[b] * 4) = split_bf16(s);
+                            if (sx) sx[(size_t)g * M + rows[b]] = s;
+                        }
+                    } else {
+                        *reinterpret_cast<uint4*>(qx + ((size_t)g * M + rows[b]) * 32 + hf * 16) = codes.lo;
+                        if (hf == 0) sx[(size_t)g * M + rows[b]] = s;
+                    }
                 }
             }
             if (LOWRANK) {
@@ -285,19 +329,32 @@ hipError_t launch_scale_chain(const float* a, float rho, int64_t n, float* s, fl
     return hipGetLastError();
 }
 
-hipError_t launch_quantize(const void* x, int64_t ldx, const float* inv_lambda, float rho,
-                           const void* l1p, int64_t M, int K, int r,
-                           uint8_t* qx, float* sx, float* h, hipStream_t stream) {
+template <bool E3M2>
+static hipError_t launch_quantize_any(const void* x, int64_t ldx, const float* inv_lambda, float rho,
+                                      const void* l1p, int64_t M, int K, int r,
+                                      uint8_t* qx, float* sx, float* h, hipStream_t stream) {
     const unsigned blocks = (unsigned)((M + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK);
     size_t lds = (size_t)K * sizeof(float);
     if (lds < (size_t)HPART_BYTES) lds = HPART_BYTES;
     if (l1p)
-        hipLaunchKernelGGL(quantize_kernel<true>, dim3(blocks), dim3(256), lds, stream,
+        hipLaunchKernelGGL((quantize_kernel<true, E3M2>), dim3(blocks), dim3(256), lds, stream,
                            (const uint16_t*)x, ldx, inv_lambda, rho, (const uint4*)l1p, M, K, r, qx, sx, h);
     else
-        hipLaunchKernelGGL(quantize_kernel<false>, dim3(blocks), dim3(256), lds, stream,
+        hipLaunchKernelGGL((quantize_kernel<false, E3M2>), dim3(blocks), dim3(256), lds, stream,
                            (const uint16_t*)x, ldx, inv_lambda, rho, (const uint4*)nullptr, M, K, r, qx, sx, h);
     return hipGetLastError();
+}
+
+hipError_t launch_quantize(const void* x, int64_t ldx, const float* inv_lambda, float rho,
+                           const void* l1p, int64_t M, int K, int r,
+                           uint8_t* qx, float* sx, float* h, hipStream_t stream) {
+    return launch_quantize_any<false>(x, ldx, inv_lambda, rho, l1p, M, K, r, qx, sx, h, stream);
+}
+
+hipError_t launch_quantize_e3m2(const void* x, int64_t ldx, const float* inv_lambda, float rho,
+                                const void* l1p, int64_t M, int K, int r,
+                                uint8_t* act, float* sx, float* h, hipStream_t stream) {
+    return launch_quantize_any<true>(x, ldx, inv_lambda, rho, l1p, M, K, r, act, sx, h, stream);
 }
 
 hipError_t launch_pack_l1(const void* L1, const float* inv_lambda, int K, int r, void* out, hipStream_t stream) {

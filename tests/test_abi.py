@@ -83,6 +83,26 @@ def test_argument_errors_before_any_launch():
     assert lib.svdq_pack_weight_mxfp4(z, a, 512, 512, a, z) == INV
     assert lib.svdq_pack_weight_mxfp4(a, a, 512, 100, a, z) == SHAPE
     assert svdq.packed_weight_mxfp4_bytes(5120, 5120) >= 5120 * 2560 and svdq.packed_weight_mxfp4_bytes(100, 5120) == 0
+    # E3M2-container execution: same conventions
+    q6 = lib.svdq_quantize_act_e3m2
+    assert q6(z, 512, a, 0.9, z, 4, 512, 0, a, a, z, z) == INV                # NULL x
+    assert q6(a, 512, a, 0.9, z, 4, 512, 0, z, a, z, z) == INV                # NULL operand buffer
+    assert q6(a, 512, a, 1.5, z, 4, 512, 0, a, z, z, z) == INV                # rho > 1
+    assert q6(a, 512, a, 0.9, z, 4, 512, 16, a, z, z, z) == INV               # r without packed L1
+    assert q6(a, 512, a, 0.9, z, 4, 480, 0, a, z, z, z) == SHAPE              # K % 64
+    assert q6(a, 512, a, 0.9, z, 0, 512, 0, a, z, z, z) == 0                  # M == 0 no-op, sx optional
+    g6 = lib.svdq_linear_w4a4_e3m2
+    assert g6(z, a, z, z, z, 4, 512, 512, 0, a, 512, 0, z) == INV
+    assert g6(a, a, a, z, z, 4, 512, 512, 16, a, 512, 0, z) == INV            # h without L2
+    assert g6(a, a, z, z, z, 4, 500, 512, 0, a, 512, 0, z) == SHAPE           # N % 128
+    assert g6(a, a, z, z, z, 0, 512, 512, 0, a, 512, 0, z) == 0
+    assert lib.svdq_pack_weight_e3m2(z, a, 512, 512, a, z) == INV
+    assert lib.svdq_pack_weight_e3m2(a, a, 512, 100, a, z) == SHAPE
+    assert lib.svdq_unpack_act_e3m2(a, 4, 100, a, z) == SHAPE
+    assert lib.svdq_unpack_act_e3m2(a, 0, 128, a, z) == 0
+    assert lib.svdq_debug_group_acc_e3m2(a, a, 4, 512, 512, 2, 8, a, z) == INV   # rows beyond M
+    assert svdq.packed_weight_e3m2_bytes(5120, 5120) == 5120 * 80 * 56 and svdq.packed_weight_e3m2_bytes(100, 5120) == 0
+    assert svdq.act_e3m2_bytes(5, 128) == 2 * 8 * 52 and svdq.act_e3m2_bytes(5, 100) == 0
     assert lib.svdq_status_string(-2) == b"unsupported shape"
 
 

@@ -167,6 +167,12 @@ def unpack_e2m1(q: np.ndarray) -> np.ndarray:
     return np.where(out & 8, -v, v).astype(np.float32)
 
 
+def pack_int4(c: np.ndarray) -> np.ndarray:
+    """[R,K] signed codes in [-8,7] -> [R,K/2] packed (even k in the low nibble)."""
+    u = (np.asarray(c).astype(np.int16) & 0xF).astype(np.uint8)
+    return (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
+
+
 def unpack_int4(q: np.ndarray) -> np.ndarray:
     """[R,K/2] packed -> [R,K] int8 signed codes."""
     lo = (q & 0xF).astype(np.int8)
