@@ -166,10 +166,11 @@ int svdq_debug_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int
  * code in memory instead of 4.  The canonical weight input is the same as for svdq_pack_weight.
  *
  * Activation operand buffer `act`, svdq_act_e3m2_bytes(M, K) bytes, device: for each 64-group g a
- * block of Mp = round_up(M, 4) rows, 52 bytes per row, in three planes
+ * block of Mp = round_up(M, 4) rows, 56 bytes per row, in three planes
  *     [Mp][2][16 B]   bytes 0..15 of the 24 code bytes of (row, 32-k half); fields ascend from bit 0
  *     [2][Mp][8 B]    bytes 16..23
- *     [Mp][4 B]       token scale s[m,g] as two bf16 pieces, hi | lo << 16 (hi + lo ~ s, 16 bits)
+ *     [Mp][8 B]       token scale s[m,g] as two bf16 pieces, p = hi | lo << 16 (hi + lo ~ s, 16 bits),
+ *                     stored twice: {p, p}
  * Rows M..Mp-1 are padding: never written, read only into results that are discarded.
  */
 size_t svdq_act_e3m2_bytes(int64_t M, int K);

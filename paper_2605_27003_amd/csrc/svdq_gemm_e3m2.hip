@@ -34,7 +34,7 @@ constexpr uint32_t OFF_A1 = 4096;      // activation codes, bytes 16..23: [half]
 constexpr uint32_t OFF_W0 = 6144;      // weight fragments, bytes 0..15:  [n-block][lane] x 16 B
 constexpr uint32_t OFF_W1 = 10240;     // weight fragments, bytes 16..23: [n-block][lane] x 8 B
 constexpr uint32_t OFF_SFR = 12288;    // n-side operand of the scale-product MFMA: [n-block][channel] x 8 B
-constexpr uint32_t OFF_SXP = 13312;    // m-side operand: [token] x 4 B (second half of the 1 KB transfer unused)
+constexpr uint32_t OFF_SXP = 13312;    // m-side operand: [token] x 8 B
 constexpr uint32_t STAGE_BYTES = 14336;
 constexpr int NSLOTS = 5;
 
@@ -98,12 +98,12 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
     const uint32_t ring0 = (uint32_t)(uintptr_t)(lds_byte*)ring;
 
     // ---- staging.  Per group the block needs 4 + 2 KB of activation codes, 4 + 2 KB of weight codes, 1 KB of
-    // weight-scale pieces and 512 B of token-scale pieces: every wave issues four 1 KB transfers (three without
+    // weight-scale pieces and 1 KB of token-scale pieces: every wave issues four 1 KB transfers (three without
     // scales).  Stream 0: bytes 0..15 of the activation fragments of (half wave / 2, tokens 64 (wave % 2) + lane).
     // Stream 1: bytes 0..15 of the weight fragments of n-block `wave`.  Stream 2: the 8-byte planes, activations
     // of half `wave` on waves 0, 1 (a lane moves two tokens), weights of n-blocks 2 (wave - 2) + {0, 1} on waves
     // 2, 3.  Stream 3: the weight-scale pieces of all four n-blocks on even waves, the token-scale pieces on odd
-    // waves (a lane moves four tokens; lanes 32..63 repeat lanes 0..31).  Waves 2, 3 repeat what waves 0, 1 move
+    // waves (a lane moves two tokens).  Waves 2, 3 repeat what waves 0, 1 move
     // there, so that every wave counts the same number of transfers and the loop has no wave-dependent branch.
     constexpr int NDMA = DUMP ? 3 : 4;
     const size_t gstride = (size_t)Mp * E3M2_ROW_BYTES;
@@ -114,7 +114,6 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
                        OFF_A0 + (uint32_t)((wave >> 1) * BM + (wave & 1) * 64) * 16};
         st[1] = Stream{w0 + (size_t)nbB * ng * 1024, 1024, (uint32_t)(wave * ng * 1024 + lane * 16), OFF_W0 + (uint32_t)wave * 1024};
         const int64_t pr = (m0 + 2 * lane < Mp - 2) ? (m0 + 2 * lane) : (Mp - 2);
-        const int64_t qr = (m0 + 4 * l32 < Mp - 4) ? (m0 + 4 * l32) : (Mp - 4);
         if (wave < 2) {
             st[2] = Stream{act + (size_t)Mp * 32 + (size_t)wave * Mp * 8, gstride, (uint32_t)(pr * 8), OFF_A1 + (uint32_t)wave * 1024};
         } else {
@@ -126,7 +125,7 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         } else if ((wave & 1) == 0) {
             st[3] = Stream{sfr + (size_t)nbB * ng * 256, 256, (uint32_t)((lane >> 4) * ng * 256 + (lane & 15) * 16), OFF_SFR};
         } else {
-            st[3] = Stream{act + (size_t)Mp * 48, gstride, (uint32_t)(qr * 4), OFF_SXP};
+            st[3] = Stream{act + (size_t)Mp * 48, gstride, (uint32_t)(pr * 8), OFF_SXP};
         }
     }
     auto stage_issue = [&](const int g) {
@@ -152,7 +151,7 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
     const uint32_t rd_w0 = OFF_W0 + (uint32_t)(wn * 2 * 64 + lane) * 16;           // + ni 1024
     const uint32_t rd_w1 = OFF_W1 + (uint32_t)(wn * 2 * 64 + lane) * 8;            // + ni 512
     const uint32_t rd_sf = OFF_SFR + (uint32_t)(wn * 2 * 32 + l32) * 8;            // + ni 256
-    const uint32_t rd_sx = OFF_SXP + (uint32_t)(wm * 64 + l32) * 4;                // + mi 128
+    const uint32_t rd_sx = OFF_SXP + (uint32_t)(wm * 64 + l32) * 8;                // + mi 256
 
     float16v y[2][2];                        // [ni][mi]
 #pragma unroll
@@ -172,12 +171,73 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         else if (k == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
         else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * NDMA) : "memory");
     };
-    // prologue: groups 0..3 requested, group 0 landed and visible
-    {
-        const int pre = ng < NSLOTS - 1 ? ng : NSLOTS - 1;
-        for (int g = 0; g < pre; ++g) stage_issue(g);
-        wait_groups(pre - 1);
+    // prologue: groups 0..3 requested; while they are in flight y starts as the low-rank term plus the bias
+    // (eq. 7, 11: the bf16 matrix cores form h L2 from hi+lo bf16 pieces of h), so that the latency of these loads
+    // hides behind the first operand transfers instead of standing at the end of the tile; then group 0 is
+    // awaited and made visible.
+    const int pre = ng < NSLOTS - 1 ? ng : NSLOTS - 1;
+    for (int g = 0; g < pre; ++g) stage_issue(g);
+    if (!DUMP) {
+        if (r > 0) {
+            const int ksteps = r >> 4;
+            for (int ks = 0; ks < ksteps; ++ks) {
+                bf16x8 lf[2];                      // L2^T fragment: row n, k = j
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    const int n = n0 + wn * 64 + ni * 32 + l32;
+                    uint32_t wds[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        uint32_t lo = L2[(int64_t)(16 * ks + 8 * kh + 2 * e) * N + n];
+                        uint32_t hi = L2[(int64_t)(16 * ks + 8 * kh + 2 * e + 1) * N + n];
+                        wds[e] = lo | (hi << 16);
+                    }
+                    uint4 t = {wds[0], wds[1], wds[2], wds[3]};
+                    lf[ni] = __builtin_bit_cast(bf16x8, t);
+                }
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) {
+                    int64_t m = m0 + wm * 64 + mi * 32 + l32;
+                    if (m >= M) m = M - 1;
+                    const float4* ph = reinterpret_cast<const float4*>(h + m * r + 16 * ks + 8 * kh);
+                    float4 h0 = ph[0], h1 = ph[1];
+                    const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+                    uint32_t hi16[8], lo16[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        hi16[e] = f_bf16_rne(hv[e]);
+                        lo16[e] = f_bf16_rne(hv[e] - bits_f(hi16[e] << 16));
+                    }
+                    uint4 th = {hi16[0] | (hi16[1] << 16), hi16[2] | (hi16[3] << 16), hi16[4] | (hi16[5] << 16), hi16[6] | (hi16[7] << 16)};
+                    uint4 tl = {lo16[0] | (lo16[1] << 16), lo16[2] | (lo16[3] << 16), lo16[4] | (lo16[5] << 16), lo16[6] | (lo16[7] << 16)};
+                    bf16x8 hhi = __builtin_bit_cast(bf16x8, th), hlo = __builtin_bit_cast(bf16x8, tl);
+#pragma unroll
+                    for (int ni = 0; ni < 2; ++ni) {
+                        y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[ni], hhi, y[ni][mi], 0, 0, 0);
+                        y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[ni], hlo, y[ni][mi], 0, 0, 0);
+                    }
+                }
+            }
+        }
+
+        // bias: channel n = 8 q + 4 kh + (i % 4) of the 32-channel tile
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * 64 + ni * 32 + 8 * q + 4 * kh;
+                float4 bv = {0.f, 0.f, 0.f, 0.f};
+                if (bias) bv = *reinterpret_cast<const float4*>(bias + n);
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) {
+                    y[ni][mi][4 * q + 0] += bv.x;
+                    y[ni][mi][4 * q + 1] += bv.y;
+                    y[ni][mi][4 * q + 2] += bv.z;
+                    y[ni][mi][4 * q + 3] += bv.w;
+                }
+            }
     }
+    wait_groups(pre - 1);
     __syncthreads();
 
     // MFMA operands of one group: code fragments (24 B per lane) and scale pieces.  Two register sets: a group's
@@ -185,21 +245,20 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
     // before), a good three tile steps ahead of their first use, into the set the current group is not using.
     struct Operands {
         uint4 xlo[2], wlo[2];
-        uint2 xhi[2], whi[2], sf[2];
-        uint32_t sxp[2];
+        uint2 xhi[2], whi[2], sf[2], sxp[2];
     };
     Operands op0, op1;
     auto fetch = [&](Operands& o, const uint32_t slot) {
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi) {
             o.xlo[mi] = lds_read16(slot + rd_x0 + mi * 512);
-            o.xhi[mi] = lds_read8(slot + rd_x1 + mi * 256);
-            if (!DUMP) o.sxp[mi] = lds_read4(slot + rd_sx + mi * 128);
+            o.xhi[mi] = lds_read8_pinned(slot + rd_x1 + mi * 256);
+            if (!DUMP) o.sxp[mi] = lds_read8(slot + rd_sx + mi * 256);
         }
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) {
             o.wlo[ni] = lds_read16(slot + rd_w0 + ni * 1024);
-            o.whi[ni] = lds_read8(slot + rd_w1 + ni * 512);
+            o.whi[ni] = lds_read8_pinned(slot + rd_w1 + ni * 512);
             if (!DUMP) o.sf[ni] = lds_read8(slot + rd_sf + ni * 256);
         }
     };
@@ -214,9 +273,8 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
     // S[n][m] = sw[n] sx[m]: n side {w1, w1, w2, w2} / 2 in both k halves, m side {x1, x2, x1, x2}
     auto smma = [&](const Operands& o, const int ni, const int mi) -> float16v {
         if (DUMP) return zero16;
-        const uint2 xs = {o.sxp[mi], o.sxp[mi]};
-        return __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, o.sf[ni]), __builtin_bit_cast(short4v, xs),
-                                                        zero16, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, o.sf[ni]),
+                                                        __builtin_bit_cast(short4v, o.sxp[mi]), zero16, 0, 0, 0);
     };
     auto fold = [&](const float16v& P, const float16v& S, float16v& yy, const int g, const int ni, const int mi) {
         if (DUMP) {
@@ -241,6 +299,14 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
     // set B tiles (0,1) and (1,1); a set is folded into y one step after its matrix instructions were issued.
     float16v PA, SA, PB = zero16, SB = zero16;  // B: tile (1,1) of the previous group, not yet folded into y
 
+    // Matrix instructions have no side effects, so the compiler places them wherever it likes inside a basic block
+    // and scheduling fences do not hold them.  This empty statement "reads" their results, which fixes the issue
+    // point of a tile's two instructions; it also passes the accumulator tile that the following fold updates, so that
+    // fold cannot be placed ahead of them.  It emits nothing.
+    auto issued = [&](const float16v& P, const float16v& S, float16v& ynext) {
+        if (!DUMP) asm volatile("" : "+v"(ynext) : "v"(P), "v"(S));
+    };
+
     // One group in slot `cur`, operands in `o`; the next group's go to `on`.  A step issues the two matrix
     // instructions of one tile and, while they run, the vector ALU folds the previous tile.  FULL: groups
     // g+1..g+4 exist, so the body is straight-line code.
@@ -252,6 +318,7 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         // step 0: tile (0,0); finishes tile (1,1) of the previous group
         PA = pmma(o, 0, 0);
         SA = smma(o, 0, 0);
+        issued(PA, SA, y[1][1]);
         fold(PB, SB, y[1][1], g - 1, 1, 1);
         __builtin_amdgcn_sched_barrier(0);
 
@@ -260,6 +327,7 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         // group g + 1, requested three groups ago, is visible after the barrier and its operands are requested.
         PB = pmma(o, 0, 1);
         SB = smma(o, 0, 1);
+        issued(PB, SB, y[0][0]);
         if (FULL || g + 1 < ng) {
             if (FULL) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
             else wait_groups((ng - 1 < g + 3 ? ng - 1 : g + 3) - (g + 1));
@@ -275,19 +343,38 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         // step 2: tile (1,0)
         PA = pmma(o, 1, 0);
         SA = smma(o, 1, 0);
+        issued(PA, SA, y[0][1]);
         fold(PB, SB, y[0][1], g, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
 
         // step 3: tile (1,1)
         PB = pmma(o, 1, 1);
         SB = smma(o, 1, 1);
+        issued(PB, SB, y[1][0]);
         fold(PA, SA, y[1][0], g, 1, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    uint32_t cur = ring0;
-    auto next_slot = [&](const uint32_t c) { return (c == ring0 + (NSLOTS - 1) * STAGE_BYTES) ? ring0 : c + STAGE_BYTES; };
+    // Main loop, ten groups per iteration (the five ring slots times the two operand sets): slot addresses are
+    // compile-time constants there, so they ride in the offset fields of the LDS instructions instead of costing
+    // vector-ALU additions per group.
+    auto slot_of = [&](const int i) { return ring0 + (uint32_t)(i % NSLOTS) * STAGE_BYTES; };
     int g = 0;
+    for (; g + 13 < ng; g += 10) {
+        group_body(g + 0, slot_of(0), slot_of(1), IC<0>{}, IC<1>{});
+        group_body(g + 1, slot_of(1), slot_of(2), IC<1>{}, IC<1>{});
+        group_body(g + 2, slot_of(2), slot_of(3), IC<0>{}, IC<1>{});
+        group_body(g + 3, slot_of(3), slot_of(4), IC<1>{}, IC<1>{});
+        group_body(g + 4, slot_of(4), slot_of(0), IC<0>{}, IC<1>{});
+        group_body(g + 5, slot_of(0), slot_of(1), IC<1>{}, IC<1>{});
+        group_body(g + 6, slot_of(1), slot_of(2), IC<0>{}, IC<1>{});
+        group_body(g + 7, slot_of(2), slot_of(3), IC<1>{}, IC<1>{});
+        group_body(g + 8, slot_of(3), slot_of(4), IC<0>{}, IC<1>{});
+        group_body(g + 9, slot_of(4), slot_of(0), IC<1>{}, IC<1>{});
+    }
+    // the rest with run-time slot addresses: complete pairs first, then the last groups with their conditions
+    uint32_t cur = ring0;                      // g is a multiple of ten here
+    auto next_slot = [&](const uint32_t c) { return (c == ring0 + (NSLOTS - 1) * STAGE_BYTES) ? ring0 : c + STAGE_BYTES; };
     for (; g + 5 < ng; g += 2) {               // two groups per iteration: the operand sets swap roles without copies
         const uint32_t nxt = next_slot(cur), nx2 = next_slot(nxt);
         group_body(g, cur, nxt, IC<0>{}, IC<1>{});
@@ -305,65 +392,7 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
 
     if (DUMP) return;
 
-    // ---- epilogue (c): low-rank up-projection on the bf16 matrix cores, bias, store
-    if (r > 0) {
-        const int ksteps = r >> 4;
-        for (int ks = 0; ks < ksteps; ++ks) {
-            bf16x8 lf[2];                      // L2^T fragment: row n, k = j
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                const int n = n0 + wn * 64 + ni * 32 + l32;
-                uint32_t wds[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    uint32_t lo = L2[(int64_t)(16 * ks + 8 * kh + 2 * e) * N + n];
-                    uint32_t hi = L2[(int64_t)(16 * ks + 8 * kh + 2 * e + 1) * N + n];
-                    wds[e] = lo | (hi << 16);
-                }
-                uint4 t = {wds[0], wds[1], wds[2], wds[3]};
-                lf[ni] = __builtin_bit_cast(bf16x8, t);
-            }
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi) {
-                int64_t m = m0 + wm * 64 + mi * 32 + l32;
-                if (m >= M) m = M - 1;
-                const float4* ph = reinterpret_cast<const float4*>(h + m * r + 16 * ks + 8 * kh);
-                float4 h0 = ph[0], h1 = ph[1];
-                const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-                uint32_t hi16[8], lo16[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    hi16[e] = f_bf16_rne(hv[e]);
-                    lo16[e] = f_bf16_rne(hv[e] - bits_f(hi16[e] << 16));
-                }
-                uint4 th = {hi16[0] | (hi16[1] << 16), hi16[2] | (hi16[3] << 16), hi16[4] | (hi16[5] << 16), hi16[6] | (hi16[7] << 16)};
-                uint4 tl = {lo16[0] | (lo16[1] << 16), lo16[2] | (lo16[3] << 16), lo16[4] | (lo16[5] << 16), lo16[6] | (lo16[7] << 16)};
-                bf16x8 hhi = __builtin_bit_cast(bf16x8, th), hlo = __builtin_bit_cast(bf16x8, tl);
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni) {
-                    y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[ni], hhi, y[ni][mi], 0, 0, 0);
-                    y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[ni], hlo, y[ni][mi], 0, 0, 0);
-                }
-            }
-        }
-    }
-
-    // bias: channel n = 8 q + 4 kh + (i % 4) of the 32-channel tile
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int n = n0 + wn * 64 + ni * 32 + 8 * q + 4 * kh;
-            float4 bv = {0.f, 0.f, 0.f, 0.f};
-            if (bias) bv = *reinterpret_cast<const float4*>(bias + n);
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi) {
-                y[ni][mi][4 * q + 0] += bv.x;
-                y[ni][mi][4 * q + 1] += bv.y;
-                y[ni][mi][4 * q + 2] += bv.z;
-                y[ni][mi][4 * q + 3] += bv.w;
-            }
-        }
+    // ---- epilogue (c): store (the low-rank term and the bias are already in y)
     const int64_t mw = m0 + wm * 64;                           // first token of this wave's tile
     if (out_f32) {
 #pragma unroll

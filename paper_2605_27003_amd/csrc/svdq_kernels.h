@@ -25,8 +25,8 @@ hipError_t launch_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, 
                             int64_t m0, int mt, int32_t* acc, hipStream_t stream);
 
 // E3M2-container variant of the int4 path (svdq_quantize.hip, svdq_gemm_e3m2.hip).  The activation operand
-// buffer holds, per 64-group, Mp = round_up(M, 4) rows of 52 bytes in three planes (see quantize_kernel).
-constexpr int E3M2_ROW_BYTES = 52;
+// buffer holds, per 64-group, Mp = round_up(M, 4) rows of 56 bytes in three planes (see quantize_kernel).
+constexpr int E3M2_ROW_BYTES = 56;
 inline size_t act_e3m2_bytes(int64_t M, int K) { return (size_t)(K / 64) * (size_t)((M + 3) & ~(int64_t)3) * E3M2_ROW_BYTES; }
 hipError_t launch_quantize_e3m2(const void* x, int64_t ldx, const float* inv_lambda, float rho,
                                 const void* l1p, int64_t M, int K, int r,

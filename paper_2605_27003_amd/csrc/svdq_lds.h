@@ -25,6 +25,10 @@ __device__ __forceinline__ uint2 lds_read8(uint32_t off) {
     const u32x2 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x2*>((lds_byte*)(uintptr_t)off);
     return uint2{v.x, v.y};
 }
+__device__ __forceinline__ uint2 lds_read8_pinned(uint32_t off) {
+    const u32x2 v = *reinterpret_cast<const volatile __attribute__((address_space(3))) u32x2*>((lds_byte*)(uintptr_t)off);
+    return uint2{v.x, v.y};
+}
 __device__ __forceinline__ uint32_t lds_read4(uint32_t off) {
     return *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>((lds_byte*)(uintptr_t)off);
 }

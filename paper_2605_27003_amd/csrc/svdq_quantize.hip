@@ -144,7 +144,8 @@ constexpr int HPART_BYTES = WAVES * ROWS_PER_BLOCK * 33 * 4;
 // per group a block of Mp rows (Mp = M rounded up to a multiple of 4; rows M..Mp-1 are never written):
 //   [Mp][2 halves][16 B]   bytes 0..15 of each lane's 24 code bytes
 //   [2 halves][Mp][8 B]    bytes 16..23
-//   [Mp] x 4 B             the token scale as two bf16 pieces (hi | lo << 16), the scale-product MFMA operand
+//   [Mp] x 8 B             the token scale as two bf16 pieces, p = hi | lo << 16, stored twice ({p, p} is the
+//                          m-side operand of the scale-product MFMA)
 // sx [K/64][M] binary32 is written in both cases (skipped if null with E3M2).
 template <bool LOWRANK, bool E3M2>
 __global__ __launch_bounds__(256, 2)
@@ -234,7 +235,8 @@ void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
                         *reinterpret_cast<uint4*>(blk + (size_t)rows[b] * 32 + hf * 16) = codes.lo;
                         *reinterpret_cast<uint2*>(blk + Mp * 32 + ((size_t)hf * Mp + rows[b]) * 8) = codes.hi;
                         if (hf == 0) {
-                            *reinterpret_cast<uint32_t*>(blk + Mp * 48 + (size_t)rows[b] * 4) = split_bf16(s);
+                            const uint32_t p = split_bf16(s);
+                            *reinterpret_cast<uint2*>(blk + Mp * 48 + (size_t)rows[b] * 8) = uint2{p, p};
                             if (sx) sx[(size_t)g * M + rows[b]] = s;
                         }
                     } else {

@@ -65,16 +65,16 @@ def pack_act_e3m2_np(codes, sx):
         if sh > 58:
             bits[..., w + 1] |= f[..., j] >> np.uint64(64 - sh)
     by = bits.view(np.uint8).reshape(M, ng, 2, 24)                 # little-endian bytes of the 24-byte fragment
-    buf = np.zeros((ng, Mp * 52), np.uint8)
+    buf = np.zeros((ng, Mp * 56), np.uint8)
     p0 = buf[:, : Mp * 32].reshape(ng, Mp, 2, 16)
     p1 = buf[:, Mp * 32: Mp * 48].reshape(ng, 2, Mp, 8)
-    p2 = buf[:, Mp * 48:].reshape(ng, Mp, 4)
+    p2 = buf[:, Mp * 48:].reshape(ng, Mp, 2, 4)
     p0[:, :M] = by[..., :16].transpose(1, 0, 2, 3)
     p1[:, :, :M] = by[..., 16:].transpose(1, 2, 0, 3)
     s = np.asarray(sx, np.float32)
     hi = synth.to_bf16_bits(s)
     lo = synth.to_bf16_bits((s - synth.bf16_bits_to_f32(hi)).astype(np.float32))
-    p2[:, :M] = (hi.astype(np.uint32) | (lo.astype(np.uint32) << 16)).T.copy().view(np.uint8).reshape(ng, M, 4)
+    p2[:, :M] = (hi.astype(np.uint32) | (lo.astype(np.uint32) << 16)).T.copy().view(np.uint8).reshape(ng, M, 1, 4)
     return buf.reshape(-1)
 
 
@@ -82,7 +82,7 @@ def unpack_act_e3m2_np(buf, M, K):
     """Host-side reader of the same buffer -> (int codes [M, K], scale pieces [M, K/64] uint32).  Fields are
     decoded from the format's definition (negative zero, which the hardware conversion can emit, is 0)."""
     ng, Mp = K // 64, (M + 3) // 4 * 4
-    buf = np.asarray(buf, np.uint8).reshape(ng, Mp * 52)
+    buf = np.asarray(buf, np.uint8).reshape(ng, Mp * 56)
     p0 = buf[:, : Mp * 32].reshape(ng, Mp, 2, 16)[:, :M]
     p1 = buf[:, Mp * 32: Mp * 48].reshape(ng, 2, Mp, 8)[:, :, :M].transpose(0, 2, 1, 3)
     by = np.concatenate([p0, p1], axis=-1)                          # [ng, M, 2, 24]
@@ -93,8 +93,9 @@ def unpack_act_e3m2_np(buf, M, K):
     codes = val.astype(np.int64)
     assert np.array_equal(codes, val), "non-integer field"
     codes = codes.transpose(1, 0, 2, 3).reshape(M, K)
-    sxp = np.ascontiguousarray(buf[:, Mp * 48:].reshape(ng, Mp, 4)[:, :M]).view(np.uint32).reshape(ng, M).T
-    return codes, sxp
+    pair = np.ascontiguousarray(buf[:, Mp * 48:].reshape(ng, Mp, 8)[:, :M]).view(np.uint32).reshape(ng, M, 2)
+    assert np.array_equal(pair[..., 0], pair[..., 1]), "scale pieces are stored twice"
+    return codes, pair[..., 0].T
 
 
 def rel_fro(a, b):

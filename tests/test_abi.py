@@ -102,7 +102,7 @@ def test_argument_errors_before_any_launch():
     assert lib.svdq_unpack_act_e3m2(a, 0, 128, a, z) == 0
     assert lib.svdq_debug_group_acc_e3m2(a, a, 4, 512, 512, 2, 8, a, z) == INV   # rows beyond M
     assert svdq.packed_weight_e3m2_bytes(5120, 5120) == 5120 * 80 * 56 and svdq.packed_weight_e3m2_bytes(100, 5120) == 0
-    assert svdq.act_e3m2_bytes(5, 128) == 2 * 8 * 52 and svdq.act_e3m2_bytes(5, 100) == 0
+    assert svdq.act_e3m2_bytes(5, 128) == 2 * 8 * 56 and svdq.act_e3m2_bytes(5, 100) == 0
     assert lib.svdq_status_string(-2) == b"unsupported shape"
 
 

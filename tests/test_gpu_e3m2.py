@@ -169,8 +169,8 @@ def test_quantise_buffer_equals_host_packer(svdq, oracle):
     Mp = (M + 3) // 4 * 4
     for g in range(K // 64):
         assert np.array_equal(got[g, Mp * 32 + M * 8: Mp * 32 + Mp * 8], np.full((Mp - M) * 8, 0xAB, np.uint8))
-        assert np.array_equal(got[g, Mp * 48 + M * 4:], np.full((Mp - M) * 4, 0xAB, np.uint8))
-        assert np.array_equal(got[g, Mp * 48: Mp * 48 + M * 4], want[g, Mp * 48: Mp * 48 + M * 4])
+        assert np.array_equal(got[g, Mp * 48 + M * 8:], np.full((Mp - M) * 8, 0xAB, np.uint8))
+        assert np.array_equal(got[g, Mp * 48: Mp * 48 + M * 8], want[g, Mp * 48: Mp * 48 + M * 8])
     gc, _ = unpack_act_e3m2_np(got.reshape(-1), M, K)
     assert np.array_equal(gc, synth.unpack_int4(oq))
     assert torch.all(buf[:64] == 0xAB) and torch.all(buf[64 + n:] == 0xAB)
