@@ -6,8 +6,10 @@ followed by the W4A4 GEMM with its fused low-rank/bias/bf16 epilogue, on the
 Wan2.2-shaped attention output projection (M=32760, K=N=5120, r=32); the
 clipping ratio cycles through the layer's four timestep bins.  Inputs are
 resident in HBM before the timed region.  Prints ONE JSON line; its headline
-fields are the int4 path, "mxfp4_variant" carries the same layer in the MXFP4
-format and "context" a dense bf16 GEMM of the same shape.
+fields are the int4 layer executed on the FP6 matrix cores (codes held as E3M2
+fields, bit-identical integer arithmetic), "int4_nibble_variant" is the same
+layer on 4-bit storage and the int8 matrix cores, "mxfp4_variant" the same
+layer in the MXFP4 format and "context" a dense bf16 GEMM of the same shape.
 """
 import argparse
 import json
@@ -20,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8 matrix peak
+FP6_MFMA_PEAK_TFLOPS = 10100.0    # MI355X dense fp6 / fp4 matrix peak
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E
 
 
@@ -88,11 +91,31 @@ def main():
     torch.cuda.set_device(0)
     svdq.load_library(build_if_missing=False)
 
-    FP4_MFMA_PEAK_TFLOPS = 10100.0    # MI355X dense fp4 matrix peak
+    FP4_MFMA_PEAK_TFLOPS = FP6_MFMA_PEAK_TFLOPS
+
+    def kernels_of(fmt, K, M, device):
+        """(weight packer, quantise call, GEMM call, activation buffers, scale bytes per token) of one execution:
+        "e3m2" = int4 codes as E3M2 fields on the FP6 matrix cores, "int4" = 4-bit storage on the int8 matrix cores,
+        "mxfp4" = the MXFP4 format."""
+        if fmt == "e3m2":
+            act = svdq.ActE3M2(torch.empty(svdq.act_e3m2_bytes(M, K), dtype=torch.uint8, device=device), M, K)
+            return (svdq.pack_weight_e3m2,
+                    lambda x, il, rho, l1p, r, h: svdq.quantize_act_e3m2(x, il, rho, l1p, r, out=(act, None, h)),
+                    lambda wp, N, h, L2, b, y: svdq.linear_w4a4_e3m2(act, wp, N, h, L2, b, out=y), 4 * (K // 64))
+        qx = torch.empty((K // 64, M, 32), dtype=torch.uint8, device=device)
+        if fmt == "int4":
+            sx = torch.empty((K // 64, M), dtype=torch.float32, device=device)
+            return (svdq.pack_weight,
+                    lambda x, il, rho, l1p, r, h: svdq.quantize_act(x, il, rho, l1p, r, out=(qx, sx, h)),
+                    lambda wp, N, h, L2, b, y: svdq.linear_w4a4(qx, sx, wp, N, h, L2, b, out=y), 4 * (K // 64))
+        sx = torch.empty(((K // 64 + 1) // 2, M, 2, 2), dtype=torch.uint8, device=device)
+        return (svdq.pack_weight_mxfp4,
+                lambda x, il, rho, l1p, r, h: svdq.quantize_act_mxfp4(x, il, rho, l1p, r, out=(qx, sx, h)),
+                lambda wp, N, h, L2, b, y: svdq.linear_mxfp4(qx, sx, wp, N, h, L2, b, out=y), K // 32)
 
     def measure(fmt):
-        """One pass of the hot path per step for the given 4-bit format; returns the timing record."""
-        w = synth.workload(args.workload, fmt=fmt)
+        """One pass of the hot path per step for the given execution; returns the timing record."""
+        w = synth.workload(args.workload, fmt="mxfp4" if fmt == "mxfp4" else "int4")
         lname = sorted(w.layers)[0]
         L = w.layers[lname]
         xname = w.inputs_of[lname.split("/")[1]]
@@ -104,26 +127,17 @@ def main():
         xs = [x0] + [x0.roll(17 * (i + 1), dims=0).contiguous() for i in range(args.xsets - 1)]
         ysets = [torch.empty((M, N), dtype=torch.bfloat16, device=x0.device) for _ in range(args.xsets)]
         h = torch.empty((M, r), dtype=torch.float32, device=x0.device)
-        qx = torch.empty((K // 64, M, 32), dtype=torch.uint8, device=x0.device)
-        if fmt == "int4":
-            wp = svdq.pack_weight(dev(L.qw), dev(L.sw))
-            sx = torch.empty((K // 64, M), dtype=torch.float32, device=x0.device)
-            quant, gemm = svdq.quantize_act, svdq.linear_w4a4
-            scale_bytes = 4 * (K // 64)
-        else:
-            wp = svdq.pack_weight_mxfp4(dev(L.qw), dev(L.sw))
-            sx = torch.empty(((K // 64 + 1) // 2, M, 2, 2), dtype=torch.uint8, device=x0.device)
-            quant, gemm = svdq.quantize_act_mxfp4, svdq.linear_mxfp4
-            scale_bytes = K // 32
+        packer, quant, gemm, scale_bytes = kernels_of(fmt, K, M, x0.device)
+        wp = packer(dev(L.qw), dev(L.sw))
 
         def step(i, ev=None):
             rho = table[i % len(table)]
             if ev:
                 ev[0].record()
-            quant(xs[i % len(xs)], inv_lambda, rho, l1p, r, out=(qx, sx, h))
+            quant(xs[i % len(xs)], inv_lambda, rho, l1p, r, h)
             if ev:
                 ev[1].record()
-            gemm(qx, sx, wp, N, h, L2, bias, out=ysets[i % len(ysets)])
+            gemm(wp, N, h, L2, bias, ysets[i % len(ysets)])
             if ev:
                 ev[2].record()
 
@@ -157,9 +171,10 @@ def main():
     def measure_block(fmt):
         """Workload with several linears (the 720p DiT block): one step = every linear's quantise pass and GEMM for the
         expert and clipping ratios of that denoising step, walking the 40-step schedule (expert switch included)."""
-        w = synth.workload(args.workload, fmt=fmt)
+        w = synth.workload(args.workload, fmt="mxfp4" if fmt == "mxfp4" else "int4")
         M = w.M
         xdev = {k: dev(v) for k, v in w.x.items()}
+        packer = {"e3m2": svdq.pack_weight_e3m2, "int4": svdq.pack_weight, "mxfp4": svdq.pack_weight_mxfp4}[fmt]
         per_expert = {}
         for ename in w.experts:
             lins = []
@@ -168,20 +183,16 @@ def main():
                 inv_lambda = dev(L.inv_lambda)
                 rec = dict(L=L, x=xdev[inp], inv_lambda=inv_lambda, L2=dev(L.L2), bias=dev(L.bias),
                            l1p=svdq.pack_lowrank_down(dev(L.L1), inv_lambda),
-                           wp=(svdq.pack_weight if fmt == "int4" else svdq.pack_weight_mxfp4)(dev(L.qw), dev(L.sw)))
+                           wp=packer(dev(L.qw), dev(L.sw)))
                 lins.append(rec)
             per_expert[ename] = lins
         bufs = {}
         for rec in per_expert[w.experts[0]]:
             K, N, r = rec["L"].K, rec["L"].N, rec["L"].r
             if (K, N) not in bufs:
-                sx = (torch.empty((K // 64, M), dtype=torch.float32, device="cuda") if fmt == "int4"
-                      else torch.empty(((K // 64 + 1) // 2, M, 2, 2), dtype=torch.uint8, device="cuda"))
-                bufs[(K, N)] = (torch.empty((K // 64, M, 32), dtype=torch.uint8, device="cuda"), sx,
-                                torch.empty((M, r), dtype=torch.float32, device="cuda"),
+                _, quant, gemm, _ = kernels_of(fmt, K, M, "cuda")
+                bufs[(K, N)] = (quant, gemm, torch.empty((M, r), dtype=torch.float32, device="cuda"),
                                 torch.empty((M, N), dtype=torch.bfloat16, device="cuda"))
-        quant = svdq.quantize_act if fmt == "int4" else svdq.quantize_act_mxfp4
-        gemm = svdq.linear_w4a4 if fmt == "int4" else svdq.linear_mxfp4
 
         def step(i, evs=None):
             t = i % w.nsteps
@@ -191,13 +202,13 @@ def main():
             rho = svdq.alpha_lookup(w.tables[w.experts[e]], t, step0, nst)
             for li, rec in enumerate(per_expert[w.experts[e]]):
                 L = rec["L"]
-                qx, sx, h, y = bufs[(L.K, L.N)]
+                quant, gemm, h, y = bufs[(L.K, L.N)]
                 if evs:
                     evs[li][0].record()
-                quant(rec["x"], rec["inv_lambda"], rho, rec["l1p"], L.r, out=(qx, sx, h))
+                quant(rec["x"], rec["inv_lambda"], rho, rec["l1p"], L.r, h)
                 if evs:
                     evs[li][1].record()
-                gemm(qx, sx, rec["wp"], L.N, h, rec["L2"], rec["bias"], out=y)
+                gemm(rec["wp"], L.N, h, rec["L2"], rec["bias"], y)
                 if evs:
                     evs[li][2].record()
 
@@ -214,88 +225,83 @@ def main():
         tq = np.array([sum(e[0].elapsed_time(e[1]) for e in ev) for ev in events])
         tg = np.array([sum(e[1].elapsed_time(e[2]) for e in ev) for ev in events])
         ops = sum(2.0 * M * rec["L"].N * rec["L"].K for rec in per_expert[w.experts[0]])
-        sb = (lambda K: 4 * (K // 64)) if fmt == "int4" else (lambda K: K // 32)
+        sb = (lambda K: K // 32) if fmt == "mxfp4" else (lambda K: 4 * (K // 64))
         bytes_q = sum(M * (2 * rec["L"].K + rec["L"].K // 2 + sb(rec["L"].K) + 4 * rec["L"].r) for rec in per_expert[w.experts[0]])
         return dict(w=w, M=M, ms_step=(t1 - t0) * 1e3 / args.steps, tq=tq, tg=tg, ops=ops, bytes_q=bytes_q, nl=nl)
 
+    METRIC = "W4A4 SVDQuant linear effective TOPS + % int8-MFMA peak; quantize pass GB/s"
+    DTYPE = ("int4 x int4 -> exact integer group sums (codes held as E3M2 fields, FP6 MFMA, binary32 accumulate), "
+             "fp32 dequant, bf16 out")
+
+    def rooflines(R, fmt, wname, launches=""):
+        """roofline objects of the GEMM and the quantise kernel of one execution."""
+        g = R["ops"] / (R["tg"].mean() * 1e-3) / 1e12
+        q = R["bytes_q"] / (R["tq"].mean() * 1e-3) / 1e9
+        gk, qk, peak, unit = {
+            "e3m2": ("svdq_linear_w4a4_e3m2 (gemm_e3m2_kernel)", "svdq_quantize_act_e3m2 (quantize_kernel)",
+                     FP6_MFMA_PEAK_TFLOPS, "TFLOP/s"),
+            "int4": ("svdq_linear_w4a4 (gemm_kernel)", "svdq_quantize_act (quantize_kernel)", INT8_MFMA_PEAK_TOPS, "TOP/s"),
+            "mxfp4": ("svdq_linear_mxfp4 (gemm_mx_kernel)", "svdq_quantize_act_mxfp4 (quantize_mx_kernel)",
+                      FP4_MFMA_PEAK_TFLOPS, "TFLOP/s")}[fmt]
+        kn = lambda k: k[k.index("(") + 1:-1]
+        rg = {"kernel": gk + launches, "bound": "mfma", "achieved": g, "peak": peak, "unit": unit, "frac": g / peak,
+              "traffic": measured_traffic(wname, kn(gk)) if wname else None,
+              "avg_ms": float(R["tg"].mean()), "min_ms": float(R["tg"].min())}
+        if fmt == "e3m2":
+            rg["frac_of_int8_peak"] = g / INT8_MFMA_PEAK_TOPS      # the same work priced at the int8 rate
+        rq = {"kernel": qk + launches, "bound": "hbm", "achieved": q, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+              "frac": q / HBM_PEAK_GBS, "traffic": measured_traffic(wname, kn(qk) + ("_e3m2" if fmt == "e3m2" else "")) if wname else None,
+              "algorithmic_bytes": R["bytes_q"], "avg_ms": float(R["tq"].mean()), "min_ms": float(R["tq"].min())}
+        return rg, rq
+
+    def variant(R, fmt, what, wname, launches=""):
+        rg, rq = rooflines(R, fmt, wname, launches)
+        v = {"what": what, "value": R["ops"] / (R["ms_step"] * 1e-3) / 1e12,
+             "unit": "TFLOP/s" if fmt == "mxfp4" else "TOPS", "ms_per_step": R["ms_step"],
+             "roofline": rg, "roofline_quantize": rq}
+        if "bf16_ms" in R:
+            v["speedup_vs_bf16_dense"] = R["bf16_ms"] / R["ms_step"]
+        return v
+
+    NIBBLE = "same int4 layer on 4-bit storage: nibbles unpacked in registers, int8 matrix cores"
+    MXFP4 = "same layer in the MXFP4 format of the paper's Table I on the block-scaled FP4 matrix instruction"
+
     if args.workload == 4:
-        recs = {"int4": measure_block("int4")}
-        if not args.skip_mxfp4:
-            recs["mxfp4"] = measure_block("mxfp4")
-        B = recs["int4"]
-        gt = B["ops"] / (B["tg"].mean() * 1e-3) / 1e12
-        qg = B["bytes_q"] / (B["tq"].mean() * 1e-3) / 1e9
+        B = measure_block("e3m2")
+        rg, rq = rooflines(B, "e3m2", None, ", six launches")
         out = {
-            "metric": "W4A4 SVDQuant linear effective TOPS + % int8-MFMA peak; quantize pass GB/s",
-            "value": B["ops"] / (B["ms_step"] * 1e-3) / 1e12, "unit": "TOPS",
+            "metric": METRIC, "value": B["ops"] / (B["ms_step"] * 1e-3) / 1e12, "unit": "TOPS",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": B["ms_step"],
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-            "dtype": "int4 x int4 -> int32 (int8 MFMA), fp32 dequant, bf16 out", "data": "synthetic",
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
             "config": {"workload": f"{B['w'].name}: M={B['M']}, six linears (q, k, v, o 5120x5120; ffn_up 5120x13824; "
                                    f"ffn_down 13824x5120) r=32, two experts over a 40-step schedule, ratio per timestep bin",
-                       "step": f"{B['nl']} x (svdq_quantize_act + svdq_linear_w4a4) = one DiT block-step"},
-            "roofline": {"kernel": "svdq_linear_w4a4 (gemm_kernel), six launches", "bound": "mfma", "achieved": gt,
-                         "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": gt / INT8_MFMA_PEAK_TOPS, "traffic": None,
-                         "avg_ms": float(B["tg"].mean()), "min_ms": float(B["tg"].min())},
-            "roofline_quantize": {"kernel": "svdq_quantize_act (quantize_kernel), six launches", "bound": "hbm",
-                                  "achieved": qg, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": qg / HBM_PEAK_GBS,
-                                  "traffic": None, "algorithmic_bytes": B["bytes_q"],
-                                  "avg_ms": float(B["tq"].mean()), "min_ms": float(B["tq"].min())},
+                       "step": f"{B['nl']} x (svdq_quantize_act_e3m2 + svdq_linear_w4a4_e3m2) = one DiT block-step"},
+            "roofline": rg, "roofline_quantize": rq,
         }
-        if "mxfp4" in recs:
-            X = recs["mxfp4"]
-            g = X["ops"] / (X["tg"].mean() * 1e-3) / 1e12
-            out["mxfp4_variant"] = {"value": X["ops"] / (X["ms_step"] * 1e-3) / 1e12, "unit": "TFLOP/s",
-                                    "ms_per_step": X["ms_step"], "gemm_TFLOPs": g, "gemm_frac_of_fp4_peak": g / FP4_MFMA_PEAK_TFLOPS,
-                                    "gemm_ms": float(X["tg"].mean()), "quantize_ms": float(X["tq"].mean())}
+        del B
+        out["int4_nibble_variant"] = variant(measure_block("int4"), "int4", NIBBLE, None, ", six launches")
+        if not args.skip_mxfp4:
+            out["mxfp4_variant"] = variant(measure_block("mxfp4"), "mxfp4", MXFP4, None, ", six launches")
         print(json.dumps(out))
         return
 
-    R = measure("int4")
+    R = measure("e3m2")
     w, L, table, M, K, N, r = R["w"], R["L"], R["table"], R["M"], R["K"], R["N"], R["r"]
-    ops, bytes_q, tq, tg, ms_step = R["ops"], R["bytes_q"], R["tq"], R["tg"], R["ms_step"]
-    gemm_tops = ops / (tg.mean() * 1e-3) / 1e12
-    quant_gbs = bytes_q / (tq.mean() * 1e-3) / 1e9
-
+    rg, rq = rooflines(R, "e3m2", w.name)
     out = {
-        "metric": "W4A4 SVDQuant linear effective TOPS + % int8-MFMA peak; quantize pass GB/s",
-        "value": ops / (ms_step * 1e-3) / 1e12, "unit": "TOPS",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int4 x int4 -> int32 (int8 MFMA), fp32 dequant, bf16 out", "data": "synthetic",
+        "metric": METRIC, "value": R["ops"] / (R["ms_step"] * 1e-3) / 1e12, "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": R["ms_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": f"{w.name}: M={M} K={K} N={N} r={r} group=64, rho per timestep bin {table}",
-                   "step": "svdq_quantize_act + svdq_linear_w4a4", "input_sets": R["nx"]},
-        "roofline": {"kernel": "svdq_linear_w4a4 (gemm_kernel)", "bound": "mfma",
-                     "achieved": gemm_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": gemm_tops / INT8_MFMA_PEAK_TOPS,
-                     "traffic": measured_traffic(w.name, "gemm_kernel"),
-                     "avg_ms": float(tg.mean()), "min_ms": float(tg.min())},
-        "roofline_quantize": {"kernel": "svdq_quantize_act (quantize_kernel)", "bound": "hbm",
-                              "achieved": quant_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": quant_gbs / HBM_PEAK_GBS,
-                              "traffic": measured_traffic(w.name, "quantize_kernel"),
-                              "algorithmic_bytes": bytes_q, "avg_ms": float(tq.mean()), "min_ms": float(tq.min())},
-        "context": {"bf16_dense_matmul_ms": R["bf16_ms"],
+                   "step": "svdq_quantize_act_e3m2 + svdq_linear_w4a4_e3m2", "input_sets": R["nx"]},
+        "roofline": rg, "roofline_quantize": rq,
+        "context": {"bf16_dense_matmul_ms": R["bf16_ms"], "speedup_vs_bf16_dense": R["bf16_ms"] / R["ms_step"],
                     "note": "vendor-library bf16 GEMM of the same shape on the same GPU (the paper's BF16 baseline)"},
     }
+    del R
+    out["int4_nibble_variant"] = variant(measure("int4"), "int4", NIBBLE, w.name)
     if not args.skip_mxfp4:
-        X = measure("mxfp4")
-        g = X["ops"] / (X["tg"].mean() * 1e-3) / 1e12
-        q = X["bytes_q"] / (X["tq"].mean() * 1e-3) / 1e9
-        out["mxfp4_variant"] = {
-            "what": "same layer in the MXFP4 format of the paper's Table I on the block-scaled FP4 matrix instruction",
-            "value": X["ops"] / (X["ms_step"] * 1e-3) / 1e12, "unit": "TFLOP/s", "ms_per_step": X["ms_step"],
-            "roofline": {"kernel": "svdq_linear_mxfp4 (gemm_mx_kernel)", "bound": "mfma", "achieved": g,
-                         "peak": FP4_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": g / FP4_MFMA_PEAK_TFLOPS,
-                         "traffic": measured_traffic(w.name, "gemm_mx_kernel"),
-                         "avg_ms": float(X["tg"].mean()), "min_ms": float(X["tg"].min())},
-            "roofline_quantize": {"kernel": "svdq_quantize_act_mxfp4 (quantize_mx_kernel)", "bound": "hbm",
-                                  "achieved": q, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": q / HBM_PEAK_GBS,
-                                  "traffic": measured_traffic(w.name, "quantize_mx_kernel"),
-                                  "algorithmic_bytes": X["bytes_q"], "avg_ms": float(X["tq"].mean()),
-                                  "min_ms": float(X["tq"].min())},
-            "speedup_vs_bf16_dense": X["bf16_ms"] / X["ms_step"]}
-        del X
+        out["mxfp4_variant"] = variant(measure("mxfp4"), "mxfp4", MXFP4, w.name)
     if args.cpu_rows > 0:
         out["cpu_baseline"] = cpu_baseline(w, L, args.cpu_rows)
     print(json.dumps(out))

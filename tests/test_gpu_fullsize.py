@@ -1,7 +1,8 @@
 """GPU-vs-oracle parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
 Rows are independent in this path, so a row sample checked against the oracle
-is exact for those rows.  Per configuration: int4 codes and scales over the
+is exact for those rows.  Both executions of the int4 layer are covered: 4-bit
+storage on the int8 matrix cores, and E3M2 fields on the FP6 matrix cores.  Per configuration: int4 codes and scales over the
 WHOLE buffers (bit-exact), h over the whole buffer, int32 group accumulators of
 the first rows and of the ragged last tile (bit-exact), and the bf16 / f32
 output on a seeded row sample (first 64, last 64, random rows).
@@ -79,6 +80,35 @@ def check_layer(svdq, oracle, name, x_bits, x_dev, L, DL, rho, n_sample, whole, 
     stats = check_y(host_bits(y16[St]), y32[St].cpu().numpy(), orc, name)
     del y32, y16
     progress(f"{name} rho={rho}: y ok on {len(S)} rows {stats}")
+
+    # The same layer with the codes held as E3M2 fields on the FP6 matrix cores (the execution bench.py times).
+    # Its operand buffer must hold exactly the codes checked above (whole buffer, compared on the device after the
+    # library's conversion back to nibbles; the sampled rows also decoded on the host straight from the documented
+    # layout), its group sums must be the oracle's, and its y meets the same bar.
+    act, _, h6 = svdq.quantize_act_e3m2(x_dev, DL.inv_lambda, rho, DL.l1p, L.r, want_sx=False)
+    assert torch.equal(svdq.unpack_act_e3m2(act), qx), f"{name}: E3M2 codes (whole buffer)"
+    assert torch.equal(h6, h), f"{name}: h of the E3M2 quantise pass"
+    Mp, ng = (M + 3) // 4 * 4, L.K // 64
+    blk = act.buf.view(ng, Mp * 56)
+    rows = torch.cat([blk[:, : Mp * 32].reshape(ng, Mp, 32)[:, St].reshape(ng, len(S), 2, 16),
+                      blk[:, Mp * 32: Mp * 48].reshape(ng, 2, Mp, 8)[:, :, St].permute(0, 2, 1, 3)], dim=-1).cpu().numpy()
+    bits = np.unpackbits(rows, axis=-1, bitorder="little").reshape(ng, len(S), 2, 32, 6)
+    f = (bits * (1 << np.arange(6))).sum(-1)
+    val = np.where((f >> 2) & 7, (4 + (f & 3)) * 2.0 ** (((f >> 2) & 7) - 5.0), (f & 3) / 16.0) * np.where(f >> 5, -1.0, 1.0)
+    assert np.array_equal(val.transpose(1, 0, 2, 3).reshape(len(S), L.K), synth.unpack_int4(oq)), f"{name}: E3M2 fields (row sample)"
+    del rows, bits, f, val
+    if whole:
+        for m0 in (0, M - acc_rows):
+            acc = svdq.debug_group_acc_e3m2(act, DL.wp6, L.N, m0, acc_rows).cpu().numpy()
+            want = oracle.group_acc(qx[:, m0:m0 + acc_rows].permute(1, 0, 2).reshape(acc_rows, -1).cpu().numpy(), L.qw)
+            assert np.array_equal(acc, want), f"{name}: E3M2 group sums rows {m0}.."
+            del acc, want
+    y16 = svdq.linear_w4a4_e3m2(act, DL.wp6, L.N, h6, DL.L2, DL.bias)
+    y32 = svdq.linear_w4a4_e3m2(act, DL.wp6, L.N, h6, DL.L2, DL.bias, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    stats = check_y(host_bits(y16[St]), y32[St].cpu().numpy(), orc, name + " e3m2")
+    del y32, y16, act
+    progress(f"{name} rho={rho}: E3M2 execution ok (codes whole buffer, y on {len(S)} rows) {stats}")
 
 
 @pytest.mark.parametrize("idx", [1, 2, 3])
