@@ -19,6 +19,7 @@
 // 24 code bytes live in two planes (bytes 0..15 and 16..23) so that LDS reads are one 16-byte and one 8-byte
 // access without bank conflicts and every transfer is a full 1 KB wave-wide load.
 #include "svdq_dev.h"
+#include "svdq_epilogue.h"
 #include "svdq_kernels.h"
 #include "svdq_lds.h"
 
@@ -177,66 +178,7 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
     // awaited and made visible.
     const int pre = ng < NSLOTS - 1 ? ng : NSLOTS - 1;
     for (int g = 0; g < pre; ++g) stage_issue(g);
-    if (!DUMP) {
-        if (r > 0) {
-            const int ksteps = r >> 4;
-            for (int ks = 0; ks < ksteps; ++ks) {
-                bf16x8 lf[2];                      // L2^T fragment: row n, k = j
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni) {
-                    const int n = n0 + wn * 64 + ni * 32 + l32;
-                    uint32_t wds[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        uint32_t lo = L2[(int64_t)(16 * ks + 8 * kh + 2 * e) * N + n];
-                        uint32_t hi = L2[(int64_t)(16 * ks + 8 * kh + 2 * e + 1) * N + n];
-                        wds[e] = lo | (hi << 16);
-                    }
-                    uint4 t = {wds[0], wds[1], wds[2], wds[3]};
-                    lf[ni] = __builtin_bit_cast(bf16x8, t);
-                }
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi) {
-                    int64_t m = m0 + wm * 64 + mi * 32 + l32;
-                    if (m >= M) m = M - 1;
-                    const float4* ph = reinterpret_cast<const float4*>(h + m * r + 16 * ks + 8 * kh);
-                    float4 h0 = ph[0], h1 = ph[1];
-                    const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-                    uint32_t hi16[8], lo16[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        hi16[e] = f_bf16_rne(hv[e]);
-                        lo16[e] = f_bf16_rne(hv[e] - bits_f(hi16[e] << 16));
-                    }
-                    uint4 th = {hi16[0] | (hi16[1] << 16), hi16[2] | (hi16[3] << 16), hi16[4] | (hi16[5] << 16), hi16[6] | (hi16[7] << 16)};
-                    uint4 tl = {lo16[0] | (lo16[1] << 16), lo16[2] | (lo16[3] << 16), lo16[4] | (lo16[5] << 16), lo16[6] | (lo16[7] << 16)};
-                    bf16x8 hhi = __builtin_bit_cast(bf16x8, th), hlo = __builtin_bit_cast(bf16x8, tl);
-#pragma unroll
-                    for (int ni = 0; ni < 2; ++ni) {
-                        y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[ni], hhi, y[ni][mi], 0, 0, 0);
-                        y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[ni], hlo, y[ni][mi], 0, 0, 0);
-                    }
-                }
-            }
-        }
-
-        // bias: channel n = 8 q + 4 kh + (i % 4) of the 32-channel tile
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * 64 + ni * 32 + 8 * q + 4 * kh;
-                float4 bv = {0.f, 0.f, 0.f, 0.f};
-                if (bias) bv = *reinterpret_cast<const float4*>(bias + n);
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi) {
-                    y[ni][mi][4 * q + 0] += bv.x;
-                    y[ni][mi][4 * q + 1] += bv.y;
-                    y[ni][mi][4 * q + 2] += bv.z;
-                    y[ni][mi][4 * q + 3] += bv.w;
-                }
-            }
-    }
+    if (!DUMP) add_lowrank_bias<2, 2>(y, h, L2, bias, m0 + wm * 64, n0 + wn * 64, M, N, r, lane);
     wait_groups(pre - 1);
     __syncthreads();
 
@@ -395,19 +337,7 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
     // ---- epilogue (c): store (the low-rank term and the bias are already in y)
     const int64_t mw = m0 + wm * 64;                           // first token of this wave's tile
     if (out_f32) {
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * 64 + ni * 32 + 8 * q + 4 * kh;
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi) {
-                    const int64_t m = mw + mi * 32 + l32;
-                    if (m >= M) continue;
-                    float4 o = {y[ni][mi][4 * q + 0], y[ni][mi][4 * q + 1], y[ni][mi][4 * q + 2], y[ni][mi][4 * q + 3]};
-                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(yout) + m * ldy + n) = o;
-                }
-            }
+        store_tile_f32<2, 2>(y, reinterpret_cast<float*>(yout), ldy, mw, n0 + wn * 64, M, lane);
     } else {
         __syncthreads();                                       // every wave is done with the operand ring
         store_tile_bf16<2>([&](int ni, int mi, int i) { return y[ni][mi][i]; },

@@ -18,6 +18,7 @@
 // v_cvt_scalef32_pk_fp4_f32 rounds two values at a time to E2M1 (nearest, ties to the even code,
 // saturating; checked against the definition on 2e5 random and all boundary inputs).
 #include "svdq_dev.h"
+#include "svdq_epilogue.h"
 #include "svdq_kernels.h"
 #include "svdq_lds.h"
 
@@ -270,10 +271,6 @@ struct MxGeom {
     static_assert(WNC == 2 || (WNC == 4 && MT == 4), "staging is written for 4 waves, or 8 waves with 256 tokens");
 };
 
-__device__ __forceinline__ uint32_t lds_read2(uint32_t off) {
-    return *reinterpret_cast<const __attribute__((address_space(3))) uint16_t*>((lds_byte*)(uintptr_t)off);
-}
-
 template <int MT, int WNC>
 __global__ __launch_bounds__(128 * WNC, (WNC == 2) ? 2 : 1)
 void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__ sxe,
@@ -460,79 +457,10 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may still be writing this block's LDS when it ends
 
     // ---- epilogue (c): low-rank up-projection on the bf16 matrix cores, bias, store
-    if (r > 0) {
-        const int ksteps = r >> 4;
-        for (int ks = 0; ks < ksteps; ++ks) {
-            bf16x8 lf[2];                      // L2^T fragment: row n, k = j
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                const int n = n0 + wn * 64 + ni * 32 + l32;
-                uint32_t wds[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    uint32_t lo = L2[(int64_t)(16 * ks + 8 * kh + 2 * e) * N + n];
-                    uint32_t hi = L2[(int64_t)(16 * ks + 8 * kh + 2 * e + 1) * N + n];
-                    wds[e] = lo | (hi << 16);
-                }
-                uint4 t = {wds[0], wds[1], wds[2], wds[3]};
-                lf[ni] = __builtin_bit_cast(bf16x8, t);
-            }
-#pragma unroll
-            for (int mi = 0; mi < MT; ++mi) {
-                int64_t m = m0 + wm * (32 * MT) + mi * 32 + l32;
-                if (m >= M) m = M - 1;
-                const float4* ph = reinterpret_cast<const float4*>(h + m * r + 16 * ks + 8 * kh);
-                float4 h0 = ph[0], h1 = ph[1];
-                const float hv[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-                uint32_t hi16[8], lo16[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    hi16[e] = f_bf16_rne(hv[e]);
-                    lo16[e] = f_bf16_rne(hv[e] - bits_f(hi16[e] << 16));
-                }
-                uint4 th = {hi16[0] | (hi16[1] << 16), hi16[2] | (hi16[3] << 16), hi16[4] | (hi16[5] << 16), hi16[6] | (hi16[7] << 16)};
-                uint4 tl = {lo16[0] | (lo16[1] << 16), lo16[2] | (lo16[3] << 16), lo16[4] | (lo16[5] << 16), lo16[6] | (lo16[7] << 16)};
-                bf16x8 hhi = __builtin_bit_cast(bf16x8, th), hlo = __builtin_bit_cast(bf16x8, tl);
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni) {
-                    y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[ni], hhi, y[ni][mi], 0, 0, 0);
-                    y[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lf[ni], hlo, y[ni][mi], 0, 0, 0);
-                }
-            }
-        }
-    }
-
-    // bias: channel n = 8 q + 4 kh + (i % 4) of the 32-channel tile
-#pragma unroll
-    for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int n = n0 + wn * 64 + ni * 32 + 8 * q + 4 * kh;
-            float4 bv = {0.f, 0.f, 0.f, 0.f};
-            if (bias) bv = *reinterpret_cast<const float4*>(bias + n);
-#pragma unroll
-            for (int mi = 0; mi < MT; ++mi) {
-                y[ni][mi][4 * q + 0] += bv.x;
-                y[ni][mi][4 * q + 1] += bv.y;
-                y[ni][mi][4 * q + 2] += bv.z;
-                y[ni][mi][4 * q + 3] += bv.w;
-            }
-        }
     const int64_t mw = m0 + wm * (32 * MT);                   // first token of this wave's tile
+    add_lowrank_bias<2, MT>(y, h, L2, bias, mw, n0 + wn * 64, M, N, r, lane);
     if (out_f32) {
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * 64 + ni * 32 + 8 * q + 4 * kh;
-#pragma unroll
-                for (int mi = 0; mi < MT; ++mi) {
-                    const int64_t m = mw + mi * 32 + l32;
-                    if (m >= M) continue;
-                    float4 o = {y[ni][mi][4 * q + 0], y[ni][mi][4 * q + 1], y[ni][mi][4 * q + 2], y[ni][mi][4 * q + 3]};
-                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(yout) + m * ldy + n) = o;
-                }
-            }
+        store_tile_f32<2, MT>(y, reinterpret_cast<float*>(yout), ldy, mw, n0 + wn * 64, M, lane);
     } else {
         __syncthreads();                                       // every wave is done with the operand ring
         uint16_t* yw = reinterpret_cast<uint16_t*>(yout) + mw * ldy + n0 + wn * 64;
