@@ -263,7 +263,11 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
     };
     auto imma = [&](const int4v& wl, const int4v& wh, const int4v& xl, const int4v& xh) -> int16v {
         int16v acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wl, xl, magic, 0, 0, 0);
-        return __builtin_amdgcn_mfma_i32_32x32x32_i8(wh, xh, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wh, xh, acc, 0, 0, 0);
+        // DUMP: keeps the matrix instructions out of the per-lane branch around the stores of their result, where
+        // they would run after operand reloads that only the active lanes perform (they read all lanes); emits nothing
+        if (DUMP) asm volatile("" ::"v"(acc));
+        return acc;
     };
     auto smma = [&](const uint2& sf, const uint2& sxv) -> float16v {
         if (DUMP) return zero16;

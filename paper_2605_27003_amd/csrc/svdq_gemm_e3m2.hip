@@ -245,8 +245,12 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
     // and scheduling fences do not hold them.  This empty statement "reads" their results, which fixes the issue
     // point of a tile's two instructions; it also passes the accumulator tile that the following fold updates, so that
     // fold cannot be placed ahead of them.  It emits nothing.
+    // In the DUMP instantiation it keeps the matrix instruction out of the per-lane branch around the stores of
+    // its result: sunk into that branch it would run after operand reloads that only the active lanes perform
+    // (the instruction itself reads all lanes).
     auto issued = [&](const float16v& P, const float16v& S, float16v& ynext) {
-        if (!DUMP) asm volatile("" : "+v"(ynext) : "v"(P), "v"(S));
+        if (DUMP) asm volatile("" ::"v"(P));
+        else asm volatile("" : "+v"(ynext) : "v"(P), "v"(S));
     };
 
     // One group in slot `cur`, operands in `o`; the next group's go to `on`.  A step issues the two matrix
