@@ -203,6 +203,23 @@ int svdq_debug_group_acc_e3m2(const uint8_t* act, const void* w_packed, int64_t 
                               int64_t m0, int mt, int32_t* acc, void* stream);
 
 /*
+ * ---- Kernel (a) with the feed-forward activation fused.  In the DiT's feed-forward block the down-projection
+ * (the module the paper calls ffn.2, one of the two most quantisation-sensitive ones, Sec. IV) reads
+ * gelu(up-projection output).  This call takes the up-projection's bf16 output x itself and applies
+ * GELU (tanh form: gelu(v) = v / (1 + exp(-2 sqrt(2/pi) (v + 0.044715 v^3)))) to every element on the fly, rounded
+ * to bf16 as a separate element-wise kernel would have stored it; everything after that is the call selected by
+ * `format` (same arguments, layouts and error behaviour; `codes` / `scales` are that call's qx / sx, act / sx or
+ * qx / sx_e8m0).  The write and the read of the activated tensor disappear.  Finite inputs.
+ */
+enum { SVDQ_FMT_INT4 = 0, SVDQ_FMT_INT4_E3M2 = 1, SVDQ_FMT_MXFP4 = 2 };
+int svdq_quantize_act_gelu(int format, const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                           const void* l1_packed, int64_t M, int K, int r,
+                           uint8_t* codes, void* scales, float* h, void* stream);
+
+/* Test hook: out_bf16[i] = bf16(gelu(x_bf16[i])) through the device function the fused pass uses; n elements. */
+int svdq_debug_gelu(const void* x_bf16, int64_t n, void* out_bf16, void* stream);
+
+/*
  * ---- MXFP4 variant: the 4-bit data format of the paper's Table I on the block-scaled
  * matrix instruction of gfx950.  Same layer (eq. 5, 7, 8, 11) and same calling conventions;
  * the integer grid of eq. 3 is replaced by microscaling FP4: blocks of 32 values along K share

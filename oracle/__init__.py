@@ -163,6 +163,18 @@ def linear(qx, sx, qw, sw, h=None, L2_bf16=None, bias=None, want=("y64", "y32", 
 
 
 # ---- MXFP4 variant -----------------------------------------------------------
+def gelu_tanh_bf16(x_bf16):
+    """bf16 bit patterns (any shape) -> bf16 bit patterns of GELU (tanh form) of each value."""
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    out = np.empty_like(x)
+    L = lib()
+    L.svdq_oracle_gelu_tanh_bf16.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    L.svdq_oracle_gelu_tanh_bf16.restype = ctypes.c_int
+    _chk(L.svdq_oracle_gelu_tanh_bf16(x.ctypes.data_as(ctypes.c_void_p), x.size, out.ctypes.data_as(ctypes.c_void_p)),
+         "gelu_tanh_bf16")
+    return out
+
+
 def e2m1_value(code):
     f = lib().svdq_oracle_e2m1_value
     f.restype = ctypes.c_float

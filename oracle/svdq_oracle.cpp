@@ -188,6 +188,40 @@ int svdq_oracle_linear(const uint8_t* qx, const float* sx,
     return 0;
 }
 
+/* GELU in its tanh form on bf16 values, result rounded to bf16: gelu(x) = x / (1 + exp(-z)),
+ * z = 2 sqrt(2/pi) (x + 0.044715 x^3).  The paper does not define the activation of the feed-forward block; this
+ * is the model's, written as a fixed sequence of binary32 operations (this file is compiled without contraction,
+ * so every line below is one correctly rounded operation) that a GPU can repeat bit for bit: exp(w) by
+ * w = n ln 2 + r with a two-piece ln 2, a degree-5 polynomial in r, and the exponent applied exactly. */
+static float gelu_tanh_f32(float x) {
+    const float u = x * x;
+    const float p = std::fmaf(0.044715f, u, 1.0f);
+    const float t = x * p;
+    const float z = 1.5957691216057308f * t;
+    float w = -z;
+    w = w < -87.0f ? -87.0f : (w > 87.0f ? 87.0f : w);
+    const float n = std::nearbyintf(w * 1.44269504088896341f);
+    float r = std::fmaf(n, -0.693359375f, w);
+    r = std::fmaf(n, 2.12194440e-4f, r);
+    float q = std::fmaf(1.9875691500e-4f, r, 1.3981999507e-3f);
+    q = std::fmaf(q, r, 8.3334519073e-3f);
+    q = std::fmaf(q, r, 4.1665795894e-2f);
+    q = std::fmaf(q, r, 1.6666665459e-1f);
+    q = std::fmaf(q, r, 5.0000001201e-1f);
+    const float rr = r * r;
+    float e = std::fmaf(q, rr, r) + 1.0f;
+    e = std::ldexp(e, (int)n);
+    const float s = 1.0f + e;
+    const float sig = (-z > 87.0f) ? 0.0f : 1.0f / s;      /* beyond the clamp exp(-z) overflows: the result is 0 */
+    return x * sig;
+}
+
+int svdq_oracle_gelu_tanh_bf16(const uint16_t* x, int64_t n, uint16_t* out) {
+    if (!x || !out || n < 0) return -1;
+    for (int64_t i = 0; i < n; ++i) out[i] = svdq_oracle_f32_to_bf16(gelu_tanh_f32(svdq_oracle_bf16_to_f32(x[i])));
+    return 0;
+}
+
 float svdq_oracle_alpha_lookup(const float* table, int nbins, int step, int step0, int nsteps_expert) {
     if (!table || nbins <= 0 || nsteps_expert <= 0) return NAN;
     int rel = step - step0;

@@ -150,6 +150,14 @@ int svdq_oracle_linear_mxfp4(const uint8_t* qx, const uint8_t* sx,
                              int64_t M, int N, int K, int r,
                              double* y64, float* y32, uint16_t* ybf16, int nthreads);
 
+/*
+ * GELU (tanh form) of bf16 values, rounded to bf16 (nearest even): the activation between the up- and the
+ * down-projection of the feed-forward block, for the quantise pass that applies it on the fly.  The paper does
+ * not define it; it is the model's activation.  out[i] = bf16(x[i] / (1 + exp(-2 sqrt(2/pi) (x[i] + 0.044715 x[i]^3)))),
+ * evaluated in binary32 by a fixed operation sequence (see the source).  Finite inputs.
+ */
+int svdq_oracle_gelu_tanh_bf16(const uint16_t* x, int64_t n, uint16_t* out);
+
 #ifdef __cplusplus
 }
 #endif

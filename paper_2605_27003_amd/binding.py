@@ -30,6 +30,8 @@ EXPORTS = {
     "svdq_pack_weight_e3m2": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
     "svdq_linear_w4a4_e3m2": (_i32, [_vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _i32, _vp]),
     "svdq_debug_group_acc_e3m2": (_i32, [_vp, _vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp]),
+    "svdq_quantize_act_gelu": (_i32, [_i32, _vp, _i64, _vp, _f32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "svdq_debug_gelu": (_i32, [_vp, _i64, _vp, _vp]),
     "svdq_quantize_act_mxfp4": (_i32, [_vp, _i64, _vp, _f32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
     "svdq_packed_weight_mxfp4_bytes": (ctypes.c_size_t, [_i32, _i32]),
     "svdq_pack_weight_mxfp4": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
@@ -256,6 +258,43 @@ def debug_group_acc_e3m2(act, w_packed, N, m0, mt):
     _check(load_library().svdq_debug_group_acc_e3m2(_ptr(act.buf), _ptr(w_packed), act.M, N, act.K, m0, mt,
                                                    _ptr(acc), _stream()), "svdq_debug_group_acc_e3m2")
     return acc
+
+
+# ---- kernel (a) with GELU fused ----------------------------------------------------------------
+FMT_INT4, FMT_INT4_E3M2, FMT_MXFP4 = 0, 1, 2
+
+
+def quantize_act_gelu(fmt, x_bf16, inv_lambda, rho, l1_packed=None, r=0, out=None):
+    """quantize_act / quantize_act_e3m2 / quantize_act_mxfp4 (fmt = FMT_*) of gelu(x), the activation applied on the
+    fly; returns what that function returns."""
+    M, K = x_bf16.shape
+    assert x_bf16.dtype == torch.bfloat16 and x_bf16.stride(1) == 1
+    dev = x_bf16.device
+    if out is None:
+        h = torch.empty((M, r), dtype=torch.float32, device=dev) if l1_packed is not None else None
+        if fmt == FMT_INT4_E3M2:
+            codes = ActE3M2(torch.empty(act_e3m2_bytes(M, K), dtype=torch.uint8, device=dev), M, K)
+            scales = torch.empty((K // 64, M), dtype=torch.float32, device=dev)
+        else:
+            codes = torch.empty((K // 64, M, 32), dtype=torch.uint8, device=dev)
+            scales = (torch.empty((K // 64, M), dtype=torch.float32, device=dev) if fmt == FMT_INT4
+                      else torch.empty(((K // 64 + 1) // 2, M, 2, 2), dtype=torch.uint8, device=dev))
+    else:
+        codes, scales, h = out
+    buf = codes.buf if fmt == FMT_INT4_E3M2 else codes
+    ldx = x_bf16.stride(0) if M > 1 else K
+    _check(load_library().svdq_quantize_act_gelu(fmt, _ptr(x_bf16), ldx, _ptr(inv_lambda), float(rho), _ptr(l1_packed),
+                                                M, K, r if l1_packed is not None else 0,
+                                                _ptr(buf), _ptr(scales), _ptr(h), _stream()), "svdq_quantize_act_gelu")
+    return codes, scales, h
+
+
+def debug_gelu(x_bf16):
+    """bf16 tensor -> bf16(gelu(x)) through the device function of the fused quantise pass."""
+    x = x_bf16.contiguous()
+    out = torch.empty_like(x)
+    _check(load_library().svdq_debug_gelu(_ptr(x), x.numel(), _ptr(out), _stream()), "svdq_debug_gelu")
+    return out
 
 
 # ---- MXFP4 variant ---------------------------------------------------------------------------

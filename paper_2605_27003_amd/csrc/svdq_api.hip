@@ -68,9 +68,9 @@ int svdq_pack_lowrank_down(const void* L1_bf16, const float* inv_lambda, int K, 
     return hip_status(svdq::launch_pack_l1(L1_bf16, inv_lambda, K, r, l1_packed, (hipStream_t)stream));
 }
 
-int svdq_quantize_act(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
-                      const void* l1_packed, int64_t M, int K, int r,
-                      uint8_t* qx, float* sx, float* h, void* stream) {
+static int quantize_nibble(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                           const void* l1_packed, int64_t M, int K, int r,
+                           uint8_t* qx, float* sx, float* h, bool gelu, void* stream) {
     if (!x_bf16 || !inv_lambda || !qx || !sx || M < 0) return SVDQ_ERR_INVALID_ARG;
     if (!(rho > 0.0f) || !(rho <= 1.0f)) return SVDQ_ERR_INVALID_ARG;      // also rejects NaN
     if (l1_packed ? (!h) : (r != 0)) return SVDQ_ERR_INVALID_ARG;
@@ -81,8 +81,14 @@ int svdq_quantize_act(const void* x_bf16, int64_t ldx, const float* inv_lambda, 
         return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
-    return hip_status(svdq::launch_quantize(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, qx, sx, h,
+    return hip_status(svdq::launch_quantize(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, qx, sx, h, gelu,
                                             (hipStream_t)stream));
+}
+
+int svdq_quantize_act(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                      const void* l1_packed, int64_t M, int K, int r,
+                      uint8_t* qx, float* sx, float* h, void* stream) {
+    return quantize_nibble(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, qx, sx, h, false, stream);
 }
 
 size_t svdq_packed_weight_bytes(int N, int K) {
@@ -152,9 +158,9 @@ size_t svdq_act_e3m2_bytes(int64_t M, int K) {
     return svdq::act_e3m2_bytes(M, K);
 }
 
-int svdq_quantize_act_e3m2(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
-                           const void* l1_packed, int64_t M, int K, int r,
-                           uint8_t* act, float* sx, float* h, void* stream) {
+static int quantize_e3m2(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                         const void* l1_packed, int64_t M, int K, int r,
+                         uint8_t* act, float* sx, float* h, bool gelu, void* stream) {
     if (!x_bf16 || !inv_lambda || !act || M < 0) return SVDQ_ERR_INVALID_ARG;
     if (!(rho > 0.0f) || !(rho <= 1.0f)) return SVDQ_ERR_INVALID_ARG;      // also rejects NaN
     if (l1_packed ? (!h) : (r != 0)) return SVDQ_ERR_INVALID_ARG;
@@ -165,8 +171,14 @@ int svdq_quantize_act_e3m2(const void* x_bf16, int64_t ldx, const float* inv_lam
         return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
-    return hip_status(svdq::launch_quantize_e3m2(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, act, sx, h,
+    return hip_status(svdq::launch_quantize_e3m2(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, act, sx, h, gelu,
                                                  (hipStream_t)stream));
+}
+
+int svdq_quantize_act_e3m2(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                           const void* l1_packed, int64_t M, int K, int r,
+                           uint8_t* act, float* sx, float* h, void* stream) {
+    return quantize_e3m2(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, act, sx, h, false, stream);
 }
 
 int svdq_unpack_act_e3m2(const uint8_t* act, int64_t M, int K, uint8_t* qx, void* stream) {
@@ -220,9 +232,9 @@ int svdq_debug_group_acc_e3m2(const uint8_t* act, const void* w_packed, int64_t 
     return hip_status(svdq::launch_group_acc_e3m2(act, w_packed, M, N, K, m0, mt, acc, (hipStream_t)stream));
 }
 
-int svdq_quantize_act_mxfp4(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
-                            const void* l1_packed, int64_t M, int K, int r,
-                            uint8_t* qx, uint8_t* sx_e8m0, float* h, void* stream) {
+static int quantize_mx(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                       const void* l1_packed, int64_t M, int K, int r,
+                       uint8_t* qx, uint8_t* sx_e8m0, float* h, bool gelu, void* stream) {
     if (!x_bf16 || !inv_lambda || !qx || !sx_e8m0 || M < 0) return SVDQ_ERR_INVALID_ARG;
     if (!(rho > 0.0f) || !(rho <= 1.0f)) return SVDQ_ERR_INVALID_ARG;
     if (l1_packed ? (!h) : (r != 0)) return SVDQ_ERR_INVALID_ARG;
@@ -233,8 +245,36 @@ int svdq_quantize_act_mxfp4(const void* x_bf16, int64_t ldx, const float* inv_la
         return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
-    return hip_status(svdq::launch_quantize_mx(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, qx, sx_e8m0, h,
+    return hip_status(svdq::launch_quantize_mx(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, qx, sx_e8m0, h, gelu,
                                                (hipStream_t)stream));
+}
+
+int svdq_quantize_act_mxfp4(const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                            const void* l1_packed, int64_t M, int K, int r,
+                            uint8_t* qx, uint8_t* sx_e8m0, float* h, void* stream) {
+    return quantize_mx(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, qx, sx_e8m0, h, false, stream);
+}
+
+int svdq_quantize_act_gelu(int format, const void* x_bf16, int64_t ldx, const float* inv_lambda, float rho,
+                           const void* l1_packed, int64_t M, int K, int r,
+                           uint8_t* codes, void* scales, float* h, void* stream) {
+    switch (format) {
+        case SVDQ_FMT_INT4:
+            return quantize_nibble(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, codes, (float*)scales, h, true, stream);
+        case SVDQ_FMT_INT4_E3M2:
+            return quantize_e3m2(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, codes, (float*)scales, h, true, stream);
+        case SVDQ_FMT_MXFP4:
+            return quantize_mx(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, codes, (uint8_t*)scales, h, true, stream);
+        default:
+            return SVDQ_ERR_INVALID_ARG;
+    }
+}
+
+int svdq_debug_gelu(const void* x_bf16, int64_t n, void* out_bf16, void* stream) {
+    if (!x_bf16 || !out_bf16 || n < 0) return SVDQ_ERR_INVALID_ARG;
+    if (n == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_gelu(x_bf16, n, out_bf16, (hipStream_t)stream));
 }
 
 size_t svdq_packed_weight_mxfp4_bytes(int N, int K) {

@@ -9,7 +9,8 @@ namespace svdq {
 // svdq_quantize.hip
 hipError_t launch_quantize(const void* x, int64_t ldx, const float* inv_lambda, float rho,
                            const void* l1p, int64_t M, int K, int r,
-                           uint8_t* qx, float* sx, float* h, hipStream_t stream);
+                           uint8_t* qx, float* sx, float* h, bool gelu, hipStream_t stream);
+hipError_t launch_gelu(const void* x, int64_t n, void* out, hipStream_t stream);
 hipError_t launch_pack_l1(const void* L1, const float* inv_lambda, int K, int r, void* out, hipStream_t stream);
 hipError_t launch_scale_chain(const float* a, float rho, int64_t n, float* s, float* inv, hipStream_t stream);
 inline size_t packed_l1_bytes(int K) { return (size_t)(K / 64) * 4 * 2 * 64 * 16; }
@@ -30,7 +31,7 @@ constexpr int E3M2_ROW_BYTES = 56;
 inline size_t act_e3m2_bytes(int64_t M, int K) { return (size_t)(K / 64) * (size_t)((M + 3) & ~(int64_t)3) * E3M2_ROW_BYTES; }
 hipError_t launch_quantize_e3m2(const void* x, int64_t ldx, const float* inv_lambda, float rho,
                                 const void* l1p, int64_t M, int K, int r,
-                                uint8_t* act, float* sx, float* h, hipStream_t stream);
+                                uint8_t* act, float* sx, float* h, bool gelu, hipStream_t stream);
 size_t packed_weight_e3m2_bytes(int N, int K);
 hipError_t launch_pack_weight_e3m2(const uint8_t* qw, const float* sw, int N, int K, void* out, hipStream_t stream);
 hipError_t launch_linear_e3m2(const uint8_t* act, const void* w_packed,
@@ -46,7 +47,7 @@ size_t packed_weight_mx_bytes(int N, int K);
 hipError_t launch_pack_weight_mx(const uint8_t* qw, const uint8_t* sw, int N, int K, void* out, hipStream_t stream);
 hipError_t launch_quantize_mx(const void* x, int64_t ldx, const float* inv_lambda, float rho,
                               const void* l1p, int64_t M, int K, int r,
-                              uint8_t* qx, uint8_t* sxe, float* h, hipStream_t stream);
+                              uint8_t* qx, uint8_t* sxe, float* h, bool gelu, hipStream_t stream);
 hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w_packed,
                             const float* h, const void* L2, const float* bias,
                             int64_t M, int N, int K, int r, void* y, int64_t ldy, int out_f32,

@@ -17,6 +17,7 @@
 // shared exponent is read off the binary32 exponent of rho * absmax (eq. 8), and
 // v_cvt_scalef32_pk_fp4_f32 rounds two values at a time to E2M1 (nearest, ties to the even code,
 // saturating; checked against the definition on 2e5 random and all boundary inputs).
+#include "svdq_act.h"
 #include "svdq_dev.h"
 #include "svdq_epilogue.h"
 #include "svdq_kernels.h"
@@ -77,7 +78,8 @@ __device__ __forceinline__ void quantize_block_mx(const uint4 (&xv)[4], const fl
 
 // Outputs: qx [K/64][M][32 B] (as the int4 path) and sxe [ceil(K/128)][M][2][2] bytes: for token m and stage s
 // (groups 2s, 2s+1) the two bytes [half h][group j] are the E8M0 scales of MX block 2 (2s + j) + h.
-template <bool LOWRANK>
+// GELU = true: every x is replaced by bf16(gelu(x)) as it arrives (svdq_act.h).
+template <bool LOWRANK, bool GELU>
 __global__ __launch_bounds__(256, 2)
 void quantize_mx_kernel(const uint16_t* __restrict__ x, int64_t ldx,
                         const float* __restrict__ inv_lambda, float rho,
@@ -154,6 +156,10 @@ void quantize_mx_kernel(const uint16_t* __restrict__ x, int64_t ldx,
         __builtin_amdgcn_sched_barrier(0);
 
         const float* il_lds = il_s + gl * 64 + hf * 32;
+        if (GELU) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b) gelu_tanh_rows(xc[b]);
+        }
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
             uint4 codes;
@@ -486,19 +492,27 @@ hipError_t launch_pack_weight_mx(const uint8_t* qw, const uint8_t* sw, int N, in
     return hipGetLastError();
 }
 
-hipError_t launch_quantize_mx(const void* x, int64_t ldx, const float* inv_lambda, float rho,
-                              const void* l1p, int64_t M, int K, int r,
-                              uint8_t* qx, uint8_t* sxe, float* h, hipStream_t stream) {
+template <bool GELU>
+static hipError_t launch_quantize_mx_any(const void* x, int64_t ldx, const float* inv_lambda, float rho,
+                                         const void* l1p, int64_t M, int K, int r,
+                                         uint8_t* qx, uint8_t* sxe, float* h, hipStream_t stream) {
     const unsigned blocks = (unsigned)((M + QROWS - 1) / QROWS);
     size_t lds = (size_t)K * sizeof(float);
     if (lds < (size_t)QHPART_BYTES) lds = QHPART_BYTES;
     if (l1p)
-        hipLaunchKernelGGL(quantize_mx_kernel<true>, dim3(blocks), dim3(256), lds, stream,
+        hipLaunchKernelGGL((quantize_mx_kernel<true, GELU>), dim3(blocks), dim3(256), lds, stream,
                            (const uint16_t*)x, ldx, inv_lambda, rho, (const uint4*)l1p, M, K, r, qx, (uint16_t*)sxe, h);
     else
-        hipLaunchKernelGGL(quantize_mx_kernel<false>, dim3(blocks), dim3(256), lds, stream,
+        hipLaunchKernelGGL((quantize_mx_kernel<false, GELU>), dim3(blocks), dim3(256), lds, stream,
                            (const uint16_t*)x, ldx, inv_lambda, rho, (const uint4*)nullptr, M, K, r, qx, (uint16_t*)sxe, h);
     return hipGetLastError();
+}
+
+hipError_t launch_quantize_mx(const void* x, int64_t ldx, const float* inv_lambda, float rho,
+                              const void* l1p, int64_t M, int K, int r,
+                              uint8_t* qx, uint8_t* sxe, float* h, bool gelu, hipStream_t stream) {
+    return gelu ? launch_quantize_mx_any<true>(x, ldx, inv_lambda, rho, l1p, M, K, r, qx, sxe, h, stream)
+                : launch_quantize_mx_any<false>(x, ldx, inv_lambda, rho, l1p, M, K, r, qx, sxe, h, stream);
 }
 
 hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w_packed,

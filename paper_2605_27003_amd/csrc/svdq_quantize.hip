@@ -17,6 +17,7 @@
 // The smoothing factor is folded into the packed L1 operand offline, so the
 // matrix cores consume the exact bf16 x; the bit-exact quantiser chain runs in
 // binary32 on the vector ALU.
+#include "svdq_act.h"
 #include "svdq_dev.h"
 #include "svdq_kernels.h"
 #include "svdq_lds.h"
@@ -147,7 +148,9 @@ constexpr int HPART_BYTES = WAVES * ROWS_PER_BLOCK * 33 * 4;
 //   [Mp] x 8 B             the token scale as two bf16 pieces, p = hi | lo << 16, stored twice ({p, p} is the
 //                          m-side operand of the scale-product MFMA)
 // sx [K/64][M] binary32 is written in both cases (skipped if null with E3M2).
-template <bool LOWRANK, bool E3M2>
+// GELU = true: x is the feed-forward block's pre-activation; every value is replaced by bf16(gelu(x)) as it
+// arrives (svdq_act.h), and the pass continues as if a separate element-wise kernel had written that tensor.
+template <bool LOWRANK, bool E3M2, bool GELU>
 __global__ __launch_bounds__(256, 2)
 void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
                      const float* __restrict__ inv_lambda, float rho,
@@ -222,6 +225,10 @@ void quantize_kernel(const uint16_t* __restrict__ x, int64_t ldx,
             __builtin_amdgcn_sched_barrier(0);
 
             const float* il_lds = il_s + g * 64 + hf * 32;
+            if (GELU) {
+#pragma unroll
+                for (int b = 0; b < 2; ++b) gelu_tanh_rows(xc[b]);
+            }
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
                 LaneCodes<E3M2> codes;
@@ -331,7 +338,7 @@ hipError_t launch_scale_chain(const float* a, float rho, int64_t n, float* s, fl
     return hipGetLastError();
 }
 
-template <bool E3M2>
+template <bool E3M2, bool GELU>
 static hipError_t launch_quantize_any(const void* x, int64_t ldx, const float* inv_lambda, float rho,
                                       const void* l1p, int64_t M, int K, int r,
                                       uint8_t* qx, float* sx, float* h, hipStream_t stream) {
@@ -339,24 +346,37 @@ static hipError_t launch_quantize_any(const void* x, int64_t ldx, const float* i
     size_t lds = (size_t)K * sizeof(float);
     if (lds < (size_t)HPART_BYTES) lds = HPART_BYTES;
     if (l1p)
-        hipLaunchKernelGGL((quantize_kernel<true, E3M2>), dim3(blocks), dim3(256), lds, stream,
+        hipLaunchKernelGGL((quantize_kernel<true, E3M2, GELU>), dim3(blocks), dim3(256), lds, stream,
                            (const uint16_t*)x, ldx, inv_lambda, rho, (const uint4*)l1p, M, K, r, qx, sx, h);
     else
-        hipLaunchKernelGGL((quantize_kernel<false, E3M2>), dim3(blocks), dim3(256), lds, stream,
+        hipLaunchKernelGGL((quantize_kernel<false, E3M2, GELU>), dim3(blocks), dim3(256), lds, stream,
                            (const uint16_t*)x, ldx, inv_lambda, rho, (const uint4*)nullptr, M, K, r, qx, sx, h);
     return hipGetLastError();
 }
 
 hipError_t launch_quantize(const void* x, int64_t ldx, const float* inv_lambda, float rho,
                            const void* l1p, int64_t M, int K, int r,
-                           uint8_t* qx, float* sx, float* h, hipStream_t stream) {
-    return launch_quantize_any<false>(x, ldx, inv_lambda, rho, l1p, M, K, r, qx, sx, h, stream);
+                           uint8_t* qx, float* sx, float* h, bool gelu, hipStream_t stream) {
+    return gelu ? launch_quantize_any<false, true>(x, ldx, inv_lambda, rho, l1p, M, K, r, qx, sx, h, stream)
+                : launch_quantize_any<false, false>(x, ldx, inv_lambda, rho, l1p, M, K, r, qx, sx, h, stream);
 }
 
 hipError_t launch_quantize_e3m2(const void* x, int64_t ldx, const float* inv_lambda, float rho,
                                 const void* l1p, int64_t M, int K, int r,
-                                uint8_t* act, float* sx, float* h, hipStream_t stream) {
-    return launch_quantize_any<true>(x, ldx, inv_lambda, rho, l1p, M, K, r, act, sx, h, stream);
+                                uint8_t* act, float* sx, float* h, bool gelu, hipStream_t stream) {
+    return gelu ? launch_quantize_any<true, true>(x, ldx, inv_lambda, rho, l1p, M, K, r, act, sx, h, stream)
+                : launch_quantize_any<true, false>(x, ldx, inv_lambda, rho, l1p, M, K, r, act, sx, h, stream);
+}
+
+// Test hook: the activation alone, through the device function the quantise kernels use.
+__global__ void gelu_kernel(const uint16_t* __restrict__ x, int64_t n, uint16_t* __restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = (uint16_t)f_bf16_rne(gelu_tanh_f32(bits_f((uint32_t)x[i] << 16)));
+}
+
+hipError_t launch_gelu(const void* x, int64_t n, void* out, hipStream_t stream) {
+    hipLaunchKernelGGL(gelu_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, (const uint16_t*)x, n, (uint16_t*)out);
+    return hipGetLastError();
 }
 
 hipError_t launch_pack_l1(const void* L1, const float* inv_lambda, int K, int r, void* out, hipStream_t stream) {

@@ -103,6 +103,14 @@ def test_argument_errors_before_any_launch():
     assert lib.svdq_debug_group_acc_e3m2(a, a, 4, 512, 512, 2, 8, a, z) == INV   # rows beyond M
     assert svdq.packed_weight_e3m2_bytes(5120, 5120) == 5120 * 80 * 56 and svdq.packed_weight_e3m2_bytes(100, 5120) == 0
     assert svdq.act_e3m2_bytes(5, 128) == 2 * 8 * 56 and svdq.act_e3m2_bytes(5, 100) == 0
+    # activation fused into kernel (a): the format selector, then that format's checks
+    qg = lib.svdq_quantize_act_gelu
+    assert qg(9, a, 512, a, 0.9, z, 4, 512, 0, a, a, z, z) == INV              # unknown format
+    for fmt in (0, 1, 2):
+        assert qg(fmt, z, 512, a, 0.9, z, 4, 512, 0, a, a, z, z) == INV        # NULL x
+        assert qg(fmt, a, 512, a, 0.9, z, 4, 480, 0, a, a, z, z) == SHAPE      # K % 64
+        assert qg(fmt, a, 512, a, 0.9, z, 0, 512, 0, a, a, z, z) == 0          # M == 0 no-op
+    assert lib.svdq_debug_gelu(z, 4, a, z) == INV and lib.svdq_debug_gelu(a, 0, a, z) == 0
     assert lib.svdq_status_string(-2) == b"unsupported shape"
 
 
