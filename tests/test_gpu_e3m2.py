@@ -206,3 +206,24 @@ def test_argument_errors(svdq):
         svdq.quantize_act_e3m2(x, il, 1.5)                       # rho out of range
     with pytest.raises(svdq.SvdqError):
         svdq.debug_group_acc_e3m2(act, wp, 128, 4, 8)            # rows beyond M
+
+
+@pytest.mark.parametrize("container", ["e3m2", "nibble"])
+def test_resident_layer_object(svdq, oracle, container):
+    """W4A4Linear (packed weights and reusable buffers behind forward()) gives the layer's output for both
+    containers, reuses its buffers for a repeated shape and re-allocates for a new one."""
+    M, K, N, r = 150, 512, 256, 32
+    x, L = small_layer(31, M, K, N, r)
+    lin = svdq.W4A4Linear(dev(L.inv_lambda), dev(L.L1), dev(L.L2), dev(L.qw), dev(L.sw), dev(L.bias), container=container)
+    y = lin.forward(dev(x), 0.9)
+    torch.cuda.synchronize()
+    oq, os_ = oracle.quantize_act(x, L.inv_lambda, 0.9)
+    orc = oracle.linear(oq, os_, L.qw, L.sw, oracle.lowrank_down(x, L.inv_lambda, L.L1), L.L2, L.bias)
+    yb = synth.bf16_bits_to_f32(host_bits(y)).astype(np.float64)
+    assert rel_fro(yb, orc["y64"]) <= 2e-3
+    ptr = y.data_ptr()
+    assert lin.forward(dev(x), 0.9).data_ptr() == ptr
+    y2 = lin.forward(dev(x[:70]), 0.9)
+    torch.cuda.synchronize()
+    assert y2.shape == (70, N) and torch.equal(y2, lin.forward(dev(x[:70]), 0.9))
+    assert rel_fro(synth.bf16_bits_to_f32(host_bits(y2)).astype(np.float64), orc["y64"][:70]) <= 2e-3
