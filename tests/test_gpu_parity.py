@@ -273,7 +273,7 @@ def test_scale_chain_every_mantissa(svdq, rho):
 def test_graph_capture_replays_match_eager(svdq):
     """The library allocates nothing and never synchronises, so a step can be captured into a HIP graph.
     Replays (with eager work and synchronisations between them) must reproduce the eager results bit for bit,
-    for both formats, on a side stream."""
+    for all three executions, on a side stream."""
     M, K, N, r = 300, 1024, 256, 32
     x, L = small_layer(17, M, K, N, r)
     DL = DeviceLayer(L)
@@ -286,9 +286,13 @@ def test_graph_capture_replays_match_eager(svdq):
     h = torch.empty((M, r), dtype=torch.float32, device="cuda")
     y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     ym = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    y6 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    act = svdq.ActE3M2(torch.empty(svdq.act_e3m2_bytes(M, K), dtype=torch.uint8, device="cuda"), M, K)
     xin = torch.empty_like(xt[0])
 
     def step():
+        svdq.quantize_act_e3m2(xin, DL.inv_lambda, 0.8, DL.l1p, r, out=(act, None, h))
+        svdq.linear_w4a4_e3m2(act, DL.wp6, N, h, DL.L2, DL.bias, out=y6)
         svdq.quantize_act(xin, DL.inv_lambda, 0.8, DL.l1p, r, out=(qx, sx, h))
         svdq.linear_w4a4(qx, sx, DL.wp, N, h, DL.L2, DL.bias, out=y)
         svdq.quantize_act_mxfp4(xin, DL.inv_lambda, 0.8, DL.l1p, r, out=(qx, sxm, h))
@@ -299,7 +303,7 @@ def test_graph_capture_replays_match_eager(svdq):
         xin.copy_(xv)
         step()
         torch.cuda.synchronize()
-        eager.append((y.clone(), ym.clone()))
+        eager.append((y.clone(), ym.clone(), y6.clone()))
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
@@ -314,10 +318,12 @@ def test_graph_capture_replays_match_eager(svdq):
         xin.copy_(xt[rep % 2])
         y.zero_()
         ym.zero_()
+        y6.zero_()
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(y, eager[rep % 2][0]) and torch.equal(ym, eager[rep % 2][1]), rep
+        assert torch.equal(y6, eager[rep % 2][2]), rep
         xin.copy_(xt[(rep + 1) % 2])                        # eager work between the replays
         step()
         torch.cuda.synchronize()
