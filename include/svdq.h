@@ -220,6 +220,28 @@ int svdq_quantize_act_gelu(int format, const void* x_bf16, int64_t ldx, const fl
 int svdq_debug_gelu(const void* x_bf16, int64_t n, void* out_bf16, void* stream);
 
 /*
+ * ---- GPTQ on the residual (Sec. III-B: the residual branch is quantised with GPTQ instead of round-to-nearest).
+ * Offline calibration.  Column-sequential form of the algorithm in binary64: weights are visited in the order
+ * k = 0..K-1; a visited weight is rounded to the int4 grid of its (channel, 64-group) scale (absmax of the group's
+ * current weights when its first weight is visited, / 7 in binary32; code = clip(rint(binary32(w) / scale), -8, 7))
+ * and its rounding error is spread over the not yet visited weights of the same channel in proportion to row k of
+ * the inverse of H + damp * mean(diag H) * I, from which index k is then eliminated.  An input channel with
+ * H[k,k] == 0 gets H[k,k] = 1 and zero weights.  With H = I and damp = 0 the result is round-to-nearest.
+ *
+ *   svdq_gptq_hessian:  H [K, K] binary64, device, += X^T X^ with X^ = x * inv_lambda (eq. 5) over the M rows of
+ *                       x_bf16 [M, ldx]; the caller zeroes H before the first calibration batch.
+ *   svdq_gptq_quantize: R [K, N] binary32 residual (row k = input channel), H as above (not modified),
+ *                       workspace of svdq_gptq_workspace_bytes(N, K) bytes (16-byte aligned, device);
+ *                       out qw [N, K/2] packed codes and sw [K/64, N] binary32 scales: the canonical weight form
+ *                       that svdq_pack_weight and svdq_pack_weight_e3m2 take.  K % 64 == 0.  Enqueues about 5 K
+ *                       small kernels on `stream`.
+ */
+size_t svdq_gptq_workspace_bytes(int N, int K);
+int svdq_gptq_hessian(const void* x_bf16, int64_t ldx, const float* inv_lambda, int64_t M, int K, double* H, void* stream);
+int svdq_gptq_quantize(const float* R, const double* H, double damp, int N, int K, void* workspace,
+                       uint8_t* qw, float* sw, void* stream);
+
+/*
  * ---- MXFP4 variant: the 4-bit data format of the paper's Table I on the block-scaled
  * matrix instruction of gfx950.  Same layer (eq. 5, 7, 8, 11) and same calling conventions;
  * the integer grid of eq. 3 is replaced by microscaling FP4: blocks of 32 values along K share

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     ActE3M2, act_e3m2_bytes, quantize_act_e3m2, unpack_act_e3m2, packed_weight_e3m2_bytes, pack_weight_e3m2,
     linear_w4a4_e3m2, debug_group_acc_e3m2,
     FMT_INT4, FMT_INT4_E3M2, FMT_MXFP4, quantize_act_gelu, debug_gelu,
+    gptq_hessian, gptq_quantize,
     sq_error, search_clipping_ratios,
     W4A4Linear,
 )

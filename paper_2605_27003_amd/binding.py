@@ -36,6 +36,9 @@ EXPORTS = {
     "svdq_packed_weight_mxfp4_bytes": (ctypes.c_size_t, [_i32, _i32]),
     "svdq_pack_weight_mxfp4": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
     "svdq_linear_mxfp4": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _i32, _vp]),
+    "svdq_gptq_workspace_bytes": (ctypes.c_size_t, [_i32, _i32]),
+    "svdq_gptq_hessian": (_i32, [_vp, _i64, _vp, _i64, _i32, _vp, _vp]),
+    "svdq_gptq_quantize": (_i32, [_vp, _vp, ctypes.c_double, _i32, _i32, _vp, _vp, _vp, _vp]),
     "svdq_sq_error_workspace_bytes": (ctypes.c_size_t, []),
     "svdq_sq_error": (_i32, [_vp, _i64, _vp, _i64, _i64, _i32, _vp, _vp, _vp]),
     "svdq_debug_group_acc": (_i32, [_vp, _vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp]),
@@ -295,6 +298,29 @@ def debug_gelu(x_bf16):
     out = torch.empty_like(x)
     _check(load_library().svdq_debug_gelu(_ptr(x), x.numel(), _ptr(out), _stream()), "svdq_debug_gelu")
     return out
+
+
+# ---- GPTQ on the residual (offline calibration) ------------------------------------------------
+def gptq_hessian(x_bf16, inv_lambda, H=None):
+    """H [K,K] f64 += X^T X^ over the rows of x (a new zero H if none is given)."""
+    M, K = x_bf16.shape
+    if H is None:
+        H = torch.zeros((K, K), dtype=torch.float64, device=x_bf16.device)
+    ldx = x_bf16.stride(0) if M > 1 else K
+    _check(load_library().svdq_gptq_hessian(_ptr(x_bf16), ldx, _ptr(inv_lambda), M, K, _ptr(H), _stream()), "svdq_gptq_hessian")
+    return H
+
+
+def gptq_quantize(R_f32, H_f64, damp=0.01):
+    """R [K,N] f32 residual, H [K,K] f64 -> (qw [N,K/2] u8 canonical codes, sw [K/64,N] f32 scales)."""
+    K, N = R_f32.shape
+    dev = R_f32.device
+    ws = torch.empty(load_library().svdq_gptq_workspace_bytes(N, K), dtype=torch.uint8, device=dev)
+    qw = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+    sw = torch.empty((K // 64, N), dtype=torch.float32, device=dev)
+    _check(load_library().svdq_gptq_quantize(_ptr(R_f32.contiguous()), _ptr(H_f64.contiguous()), float(damp), N, K,
+                                            _ptr(ws), _ptr(qw), _ptr(sw), _stream()), "svdq_gptq_quantize")
+    return qw, sw
 
 
 # ---- MXFP4 variant ---------------------------------------------------------------------------

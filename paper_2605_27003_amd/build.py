@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsvdq.so")
-SOURCES = ["svdq_api.hip", "svdq_quantize.hip", "svdq_gemm.hip", "svdq_gemm_e3m2.hip", "svdq_lowrank.hip", "svdq_mxfp4.hip", "svdq_search.hip"]
+SOURCES = ["svdq_api.hip", "svdq_quantize.hip", "svdq_gemm.hip", "svdq_gemm_e3m2.hip", "svdq_lowrank.hip", "svdq_mxfp4.hip", "svdq_search.hip", "svdq_gptq.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 vector ops stay disabled: plain v_fma_f32 / v_mul_f32 only
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

@@ -309,6 +309,29 @@ int svdq_linear_mxfp4(const uint8_t* qx, const uint8_t* sx_e8m0, const void* w_p
                                              out_dtype == SVDQ_OUT_F32, (hipStream_t)stream));
 }
 
+size_t svdq_gptq_workspace_bytes(int N, int K) {
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP) return 0;
+    return svdq::gptq_workspace_bytes(N, K);
+}
+
+int svdq_gptq_hessian(const void* x_bf16, int64_t ldx, const float* inv_lambda, int64_t M, int K, double* H, void* stream) {
+    if (!x_bf16 || !inv_lambda || !H || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (K <= 0 || K % SVDQ_GROUP || ldx < K) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_gptq_hessian(x_bf16, ldx, inv_lambda, M, K, H, (hipStream_t)stream));
+}
+
+int svdq_gptq_quantize(const float* R, const double* H, double damp, int N, int K, void* workspace,
+                       uint8_t* qw, float* sw, void* stream) {
+    if (!R || !H || !workspace || !qw || !sw) return SVDQ_ERR_INVALID_ARG;
+    if (!(damp >= 0.0)) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(workspace)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_gptq_quantize(R, H, damp, N, K, workspace, qw, sw, (hipStream_t)stream));
+}
+
 size_t svdq_sq_error_workspace_bytes(void) { return (size_t)svdq::SQ_ERROR_PARTIALS * sizeof(double); }
 
 int svdq_sq_error(const void* y_ref_bf16, int64_t ld_ref, const void* y_bf16, int64_t ldy,

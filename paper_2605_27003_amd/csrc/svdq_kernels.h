@@ -58,6 +58,13 @@ constexpr int SQ_ERROR_PARTIALS = 1024;
 hipError_t launch_sq_error(const void* yref, int64_t ldr, const void* y, int64_t ldy, int64_t M, int N,
                            double* workspace, double* out, hipStream_t stream);
 
+// svdq_gptq.hip (offline calibration)
+size_t gptq_workspace_bytes(int N, int K);
+hipError_t launch_gptq_hessian(const void* x, int64_t ldx, const float* inv_lambda, int64_t M, int K, double* H,
+                               hipStream_t stream);
+hipError_t launch_gptq_quantize(const float* R, const double* H, double damp, int N, int K, void* workspace,
+                                uint8_t* qw, float* sw, hipStream_t stream);
+
 // svdq_lowrank.hip
 hipError_t launch_lowrank_down(const void* x, int64_t ldx, const float* inv_lambda, const void* L1,
                                int64_t M, int K, int r, float* h, hipStream_t stream);

@@ -111,6 +111,14 @@ def test_argument_errors_before_any_launch():
         assert qg(fmt, a, 512, a, 0.9, z, 4, 480, 0, a, a, z, z) == SHAPE      # K % 64
         assert qg(fmt, a, 512, a, 0.9, z, 0, 512, 0, a, a, z, z) == 0          # M == 0 no-op
     assert lib.svdq_debug_gelu(z, 4, a, z) == INV and lib.svdq_debug_gelu(a, 0, a, z) == 0
+    # GPTQ calibration
+    assert lib.svdq_gptq_workspace_bytes(128, 100) == 0 and lib.svdq_gptq_workspace_bytes(128, 128) >= 128 * 128 * 17
+    assert lib.svdq_gptq_hessian(z, 128, a, 4, 128, a, z) == INV
+    assert lib.svdq_gptq_hessian(a, 64, a, 4, 128, a, z) == SHAPE               # ldx < K
+    assert lib.svdq_gptq_hessian(a, 128, a, 0, 128, a, z) == 0
+    assert lib.svdq_gptq_quantize(a, a, -1.0, 128, 128, a, a, a, z) == INV      # negative damping
+    assert lib.svdq_gptq_quantize(a, a, 0.01, 128, 100, a, a, a, z) == SHAPE
+    assert lib.svdq_gptq_quantize(a, z, 0.01, 128, 128, a, a, a, z) == INV
     assert lib.svdq_status_string(-2) == b"unsupported shape"
 
 
