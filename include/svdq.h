@@ -197,6 +197,29 @@ int svdq_linear_w4a4_e3m2(const uint8_t* act, const void* w_packed,
                           int64_t M, int N, int K, int r,
                           void* y, int64_t ldy, int out_dtype, void* stream);
 
+/* Two layers fused across their boundary (the feed-forward block: up-projection, GELU,
+ * down-projection; eq. 7 and 11 of the first layer followed by eq. 5, 8, 9, 3 and the low-rank
+ * down-projection of eq. 7 of the second).  svdq_linear_w4a4_e3m2 of the first layer, but y never
+ * reaches memory: each 64 x 64 tile is rounded to bf16 (the value svdq_linear_w4a4_e3m2 would have
+ * stored), passed through GELU if `gelu` != 0 (as svdq_quantize_act_gelu defines it), and quantised
+ * for the NEXT layer, whose K axis is this layer's N.  The result is what
+ *     svdq_linear_w4a4_e3m2(..., y bf16) ; svdq_quantize_act[_gelu](E3M2, y, next_*)
+ * writes: next_act and next_sx bit for bit, next_h up to summation order.
+ *   next_inv_lambda [N] binary32, next_rho in (0, 1]: the next layer's smoothing vector and clipping ratio.
+ *   next_l1_packed  svdq_pack_lowrank_down(L1' [N, next_r], next_inv_lambda) or NULL (then next_r = 0,
+ *                   next_h unused).
+ *   next_act  out, svdq_act_e3m2_bytes(M, N) bytes.  next_sx out [N/64][M] binary32 or NULL.
+ *   next_h    out [M, next_r] binary32.  Zeroed by the call, then every tile adds its 64-channel share
+ *             with floating-point atomic adds: the summation order, hence the last bits, vary from
+ *             run to run (the separate quantise kernel sums in a fixed order).
+ * Shapes, alignment and error behaviour as svdq_linear_w4a4_e3m2 and svdq_quantize_act_e3m2. */
+int svdq_linear_w4a4_e3m2_next(const uint8_t* act, const void* w_packed,
+                               const float* h, const void* L2_bf16, const float* bias,
+                               int64_t M, int N, int K, int r, int gelu,
+                               const float* next_inv_lambda, float next_rho,
+                               const void* next_l1_packed, int next_r,
+                               uint8_t* next_act, float* next_sx, float* next_h, void* stream);
+
 /* Test hook: the integer group sums as the FP6 matrix-core path forms them; acc out [mt, N, K/64]
  * int32, rows [m0, m0 + mt) as for svdq_debug_group_acc. */
 int svdq_debug_group_acc_e3m2(const uint8_t* act, const void* w_packed, int64_t M, int N, int K,

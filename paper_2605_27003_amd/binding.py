@@ -29,6 +29,8 @@ EXPORTS = {
     "svdq_packed_weight_e3m2_bytes": (ctypes.c_size_t, [_i32, _i32]),
     "svdq_pack_weight_e3m2": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
     "svdq_linear_w4a4_e3m2": (_i32, [_vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _i32, _vp]),
+    "svdq_linear_w4a4_e3m2_next": (_i32, [_vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _i32,
+                                          _vp, _f32, _vp, _i32, _vp, _vp, _vp, _vp]),
     "svdq_debug_group_acc_e3m2": (_i32, [_vp, _vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp]),
     "svdq_quantize_act_gelu": (_i32, [_i32, _vp, _i64, _vp, _f32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _vp]),
     "svdq_debug_gelu": (_i32, [_vp, _i64, _vp, _vp]),
@@ -253,6 +255,28 @@ def linear_w4a4_e3m2(act, w_packed, N, h=None, L2_bf16=None, bias=None, out=None
     _check(load_library().svdq_linear_w4a4_e3m2(_ptr(act.buf), _ptr(w_packed), _ptr(h), _ptr(L2_bf16), _ptr(bias),
                                                M, N, K, r, _ptr(out), ldy, code, _stream()), "svdq_linear_w4a4_e3m2")
     return out
+
+
+def linear_w4a4_e3m2_next(act, w_packed, N, next_inv_lambda, next_rho, h=None, L2_bf16=None, bias=None, gelu=True,
+                          next_l1_packed=None, next_r=0, out=None, want_sx=True):
+    """The layer on `act` fused with the NEXT layer's quantise pass (optionally through GELU): returns what
+    quantize_act_e3m2 / quantize_act_gelu(FMT_INT4_E3M2) of this layer's bf16 output would return,
+    (ActE3M2 of shape [M, N], sx [N/64, M] or None, h' [M, next_r] or None), without y ever being stored."""
+    M, K = act.M, act.K
+    r = 0 if h is None else h.shape[1]
+    dev = act.buf.device
+    if out is None:
+        nact = ActE3M2(torch.empty(act_e3m2_bytes(M, N), dtype=torch.uint8, device=dev), M, N)
+        nsx = torch.empty((N // 64, M), dtype=torch.float32, device=dev) if want_sx else None
+        nh = torch.empty((M, next_r), dtype=torch.float32, device=dev) if next_l1_packed is not None else None
+    else:
+        nact, nsx, nh = out
+        assert nact.M == M and nact.K == N
+    _check(load_library().svdq_linear_w4a4_e3m2_next(
+        _ptr(act.buf), _ptr(w_packed), _ptr(h), _ptr(L2_bf16), _ptr(bias), M, N, K, r, int(bool(gelu)),
+        _ptr(next_inv_lambda), float(next_rho), _ptr(next_l1_packed), next_r if next_l1_packed is not None else 0,
+        _ptr(nact.buf), _ptr(nsx), _ptr(nh), _stream()), "svdq_linear_w4a4_e3m2_next")
+    return nact, nsx, nh
 
 
 def debug_group_acc_e3m2(act, w_packed, N, m0, mt):

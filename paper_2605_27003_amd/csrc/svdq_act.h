@@ -27,7 +27,7 @@ __device__ __forceinline__ float gelu_tanh_f32(float x) {
 
 // two bf16 values in a dword -> gelu of both, rounded to bf16 (nearest even)
 __device__ __forceinline__ uint32_t gelu_tanh_bf16x2(uint32_t w) {
-    return f_bf16_rne(gelu_tanh_f32(bf16lo_f(w))) | (f_bf16_rne(gelu_tanh_f32(bf16hi_f(w))) << 16);
+    return f2_bf16_rne(gelu_tanh_f32(bf16lo_f(w)), gelu_tanh_f32(bf16hi_f(w)));
 }
 
 // the 32 values a lane holds of one 64-group

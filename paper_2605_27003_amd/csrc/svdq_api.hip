@@ -222,6 +222,29 @@ int svdq_linear_w4a4_e3m2(const uint8_t* act, const void* w_packed,
                                                out_dtype == SVDQ_OUT_F32, (hipStream_t)stream));
 }
 
+int svdq_linear_w4a4_e3m2_next(const uint8_t* act, const void* w_packed,
+                               const float* h, const void* L2_bf16, const float* bias,
+                               int64_t M, int N, int K, int r, int gelu,
+                               const float* next_inv_lambda, float next_rho,
+                               const void* next_l1_packed, int next_r,
+                               uint8_t* next_act, float* next_sx, float* next_h, void* stream) {
+    if (!act || !w_packed || !next_inv_lambda || !next_act || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (r == 0 ? (h || L2_bf16) : (!h || !L2_bf16)) return SVDQ_ERR_INVALID_ARG;
+    if (!(next_rho > 0.0f) || !(next_rho <= 1.0f)) return SVDQ_ERR_INVALID_ARG;
+    if (next_l1_packed ? (!next_h) : (next_r != 0)) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if ((r != 0 && !rank_ok(r)) || (next_l1_packed && !rank_ok(next_r))) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(act) || !aligned16(w_packed) || !aligned16(h) || !aligned16(L2_bf16) || !aligned16(bias) ||
+        !aligned16(next_inv_lambda) || !aligned16(next_l1_packed) || !aligned16(next_act) || !aligned16(next_sx) ||
+        (next_l1_packed && !aligned16(next_h)))
+        return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_linear_e3m2_next(act, w_packed, h, L2_bf16, bias, M, N, K, r, gelu != 0,
+                                                    next_inv_lambda, next_rho, next_l1_packed, next_r,
+                                                    next_act, next_sx, next_h, (hipStream_t)stream));
+}
+
 int svdq_debug_group_acc_e3m2(const uint8_t* act, const void* w_packed, int64_t M, int N, int K,
                               int64_t m0, int mt, int32_t* acc, void* stream) {
     if (!act || !w_packed || !acc || M < 0 || m0 < 0 || mt < 0 || m0 + mt > M) return SVDQ_ERR_INVALID_ARG;

@@ -66,14 +66,14 @@ __device__ __forceinline__ void add_lowrank_bias(float16v (&y)[NI][MT], const fl
             for (int mi = 0; mi < MT; ++mi) {
                 const float4 h0 = hv[ks][mi][0], h1 = hv[ks][mi][1];
                 const float v[8] = {h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
-                uint32_t hi16[8], lo16[8];
+                uint32_t hp[4], lp[4];                       // pairs of hi pieces, pairs of lo pieces
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    hi16[e] = f_bf16_rne(v[e]);
-                    lo16[e] = f_bf16_rne(v[e] - bits_f(hi16[e] << 16));
+                for (int e = 0; e < 4; ++e) {
+                    hp[e] = f2_bf16_rne(v[2 * e], v[2 * e + 1]);
+                    lp[e] = f2_bf16_rne(v[2 * e] - bf16lo_f(hp[e]), v[2 * e + 1] - bf16hi_f(hp[e]));
                 }
-                const uint4 th = {hi16[0] | (hi16[1] << 16), hi16[2] | (hi16[3] << 16), hi16[4] | (hi16[5] << 16), hi16[6] | (hi16[7] << 16)};
-                const uint4 tl = {lo16[0] | (lo16[1] << 16), lo16[2] | (lo16[3] << 16), lo16[4] | (lo16[5] << 16), lo16[6] | (lo16[7] << 16)};
+                const uint4 th = {hp[0], hp[1], hp[2], hp[3]};
+                const uint4 tl = {lp[0], lp[1], lp[2], lp[3]};
                 const uint4 z = {0u, 0u, 0u, 0u};             // an unused k-step multiplies 0 by 0, whatever h holds
                 const bf16x8 hhi = __builtin_bit_cast(bf16x8, on ? th : z), hlo = __builtin_bit_cast(bf16x8, on ? tl : z);
 #pragma unroll

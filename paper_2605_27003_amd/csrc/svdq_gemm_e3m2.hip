@@ -18,10 +18,12 @@
 // direct global->LDS loads into a five-slot ring of one-group stages, requested four groups ahead.  A lane's
 // 24 code bytes live in two planes (bytes 0..15 and 16..23) so that LDS reads are one 16-byte and one 8-byte
 // access without bank conflicts and every transfer is a full 1 KB wave-wide load.
+#include "svdq_act.h"
 #include "svdq_dev.h"
 #include "svdq_epilogue.h"
 #include "svdq_kernels.h"
 #include "svdq_lds.h"
+#include "svdq_quant_dev.h"
 
 namespace svdq {
 
@@ -68,14 +70,37 @@ struct Stream {
     uint32_t lds;
 };
 
-// DUMP = false: the layer.  DUMP = true: write the integer group sums of rows [dm0, dm0 + dmt) instead of y.
-template <bool DUMP>
+// What the kernel does with the finished tile.
+//   MODE_LAYER      store y (bf16 or binary32): the layer.
+//   MODE_DUMP       test hook: write the integer group sums of rows [dm0, dm0 + dmt) instead of y.
+//   MODE_NEXT       y never reaches HBM: the wave rounds its 64 x 64 tile to bf16 (what MODE_LAYER would have
+//   MODE_NEXT_GELU  stored), optionally applies GELU, and runs the NEXT layer's quantise pass on it: a wave's 64
+//                   channels are exactly one 64-group of the next layer's K axis, so it writes that group's block
+//                   of the next activation operand buffer (codes, scale pieces, optionally sx) and adds its share
+//                   of the next low-rank projection h' = x^' L1' to the (zeroed) binary32 h' with atomic adds.
+enum { MODE_LAYER = 0, MODE_DUMP = 1, MODE_NEXT = 2, MODE_NEXT_GELU = 3 };
+
+// The next layer's side of MODE_NEXT*: smoothing vector [N], clipping ratio, packed L1' (pack_l1_kernel order,
+// K' = N) and rank, outputs.
+struct NextLayer {
+    const float* inv_lambda;
+    const uint4* l1p;
+    uint8_t* act;
+    float* sx;
+    float* h;
+    float rho;
+    int r;
+};
+
+template <int MODE>
 __global__ __launch_bounds__(256, 2)
 void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict__ w0, const uint8_t* __restrict__ w1,
                       const uint8_t* __restrict__ sfr,
                       const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
                       int64_t M, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
-                      int tile0, int mtiles, int ntiles, int64_t dm0, int dmt, int32_t* __restrict__ dacc) {
+                      int tile0, int mtiles, int ntiles, int64_t dm0, int dmt, int32_t* __restrict__ dacc,
+                      const NextLayer nx) {
+    constexpr bool DUMP = MODE == MODE_DUMP, NEXT = MODE >= MODE_NEXT, GELU = MODE == MODE_NEXT_GELU;
     __shared__ __attribute__((aligned(16))) uint8_t ring[NSLOTS * STAGE_BYTES];   // slot of group g: g % 5
 
     // XCD-aware tile order: consecutive block ids go round-robin to the 8 XCDs, so give each XCD its own token
@@ -338,8 +363,103 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
 
     if (DUMP) return;
 
-    // ---- epilogue (c): store (the low-rank term and the bias are already in y)
     const int64_t mw = m0 + wm * 64;                           // first token of this wave's tile
+    if constexpr (NEXT) {
+        // ---- the next layer's kernel (a) on this wave's tile.  Lane (l32, kh) holds, of token mw + 32 mi + l32,
+        // channels 32 ni + 8 q + 4 kh + j (register 4 q + j of y[ni][mi]).  After rounding (and GELU) the values
+        // are packed in pairs and the lanes l, l + 32 trade n-blocks: lane kh keeps the 32 consecutive channels
+        // 32 kh .. 32 kh + 31 of its token, which is the lane layout of the quantise kernel (and the A operand of
+        // the bf16 matrix instruction that forms h').
+        const int gq = (n0 + wn * 64) >> 6;                    // this wave's group of the next layer
+        const float* il = nx.inv_lambda + n0 + wn * 64 + kh * 32;
+        uint4 bfrag[4][2];
+        if (nx.r > 0) {
+            const uint4* pb = nx.l1p + (size_t)gq * (4 * 2 * 64) + lane;
+#pragma unroll
+            for (int sI = 0; sI < 4; ++sI) {
+                bfrag[sI][0] = pb[(sI * 2 + 0) * 64];
+                bfrag[sI][1] = pb[(sI * 2 + 1) * 64];
+            }
+        }
+        uint8_t* blk = nx.act + (size_t)gq * Mp * E3M2_ROW_BYTES;
+        float16v hp[2];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+            uint32_t pk[2][8];
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int d = 0; d < 8; ++d) {
+                    uint32_t w = f2_bf16_rne(y[ni][mi][2 * d], y[ni][mi][2 * d + 1]);
+                    if (GELU) w = gelu_tanh_bf16x2(w);
+                    pk[ni][d] = w;
+                }
+            uint4 xc[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                // first result: own value in lanes 0..31, the lower lanes' second operand in lanes 32..63;
+                // second result: the upper lanes' first operand in lanes 0..31, own value in lanes 32..63
+                const auto e0 = __builtin_amdgcn_permlane32_swap(pk[0][2 * q], pk[1][2 * q], false, false);
+                const auto e1 = __builtin_amdgcn_permlane32_swap(pk[0][2 * q + 1], pk[1][2 * q + 1], false, false);
+                xc[q] = uint4{e0[0], e1[0], e0[1], e1[1]};     // channels 32 kh + 8 q + 0..7
+            }
+            LaneCodes<true> codes;
+            float sc;
+            quantize_rows<true>(xc, il, nx.rho, codes, sc);
+            const int64_t row = mw + mi * 32 + l32;
+            if (row < M) {
+                *reinterpret_cast<uint4*>(blk + (size_t)row * 32 + kh * 16) = codes.lo;
+                *reinterpret_cast<uint2*>(blk + (size_t)Mp * 32 + ((size_t)kh * Mp + row) * 8) = codes.hi;
+                if (kh == 0) {
+                    const uint32_t p = split_bf16(sc);
+                    *reinterpret_cast<uint2*>(blk + (size_t)Mp * 48 + (size_t)row * 8) = uint2{p, p};
+                    if (nx.sx) nx.sx[(size_t)gq * M + row] = sc;
+                }
+            }
+            if (nx.r > 0) {
+                hp[mi] = zero16;                               // [token][j]: lane holds column j = l32
+#pragma unroll
+                for (int sI = 0; sI < 4; ++sI) {
+                    const bf16x8 av = __builtin_bit_cast(bf16x8, xc[sI]);
+                    hp[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sI][0]), hp[mi], 0, 0, 0);
+                    hp[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sI][1]), hp[mi], 0, 0, 0);
+                }
+            }
+        }
+        if (nx.r > 0) {
+            // the two waves that share tokens (wn = 0, 1) add their shares in LDS first: half the atomic adds
+            __syncthreads();                                   // every wave is done with the operand ring
+            float* part = reinterpret_cast<float*>(ring) + wm * (2 * 16 * 64) + lane;
+            if (wn == 1) {
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) part[(mi * 16 + i) * 64] = hp[mi][i];
+            }
+            __syncthreads();
+            if (wn == 0) {
+                float tot[2][16];                              // all LDS reads first: one wait, not one per add
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) tot[mi][i] = hp[mi][i] + part[(mi * 16 + i) * 64];
+                // register (mi, i) is token mw + 4 kh + [32 mi + 8 (i / 4) + i % 4] of column l32
+                const int64_t first = mw + 4 * kh;
+                const int left = (l32 < nx.r && first < M) ? (int)((M - first < 64) ? M - first : 64) : 0;
+                float* hb = nx.h + first * nx.r + l32;
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int rl = 32 * mi + 8 * (i >> 2) + (i & 3);
+                        if (rl < left) unsafeAtomicAdd(hb + rl * nx.r, tot[mi][i]);
+                    }
+            }
+        }
+        return;
+    }
+
+    // ---- epilogue (c): store (the low-rank term and the bias are already in y)
     if (out_f32) {
         store_tile_f32<2, 2>(y, reinterpret_cast<float*>(yout), ldy, mw, n0 + wn * 64, M, lane);
     } else {
@@ -418,6 +538,13 @@ __global__ void unpack_act_e3m2_kernel(const uint8_t* __restrict__ act, int64_t 
     }
 }
 
+// h' of the emitting modes starts at zero.  A kernel, not a memset: memset nodes misbehave in replayed graphs.
+__global__ void zero_f32_kernel(float* __restrict__ p, int64_t n) {
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i + 4 <= n) *reinterpret_cast<float4*>(p + i) = float4{0.f, 0.f, 0.f, 0.f};
+    else for (int64_t j = i; j < n; ++j) p[j] = 0.f;
+}
+
 static inline unsigned grid_for(int mtiles, int ntiles) {
     const int sms = (mtiles + 63) / 64;          // super-stripes of 8 XCDs x 8 token tiles
     return (unsigned)(sms * 64 * ntiles);
@@ -443,10 +570,30 @@ hipError_t launch_linear_e3m2(const uint8_t* act, const void* w_packed,
                               hipStream_t stream) {
     const int mtiles = (int)((M + BM - 1) / BM), ntiles = N / BN;
     const uint8_t* base = (const uint8_t*)w_packed;
-    hipLaunchKernelGGL(gemm_e3m2_kernel<false>, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
+    hipLaunchKernelGGL(gemm_e3m2_kernel<MODE_LAYER>, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
                        act, base, base + w0_bytes(N, K), base + w0_bytes(N, K) + w1_bytes(N, K),
                        h, (const uint16_t*)L2, bias, M, N, K, r, y, ldy, out_f32,
-                       0, mtiles, ntiles, (int64_t)0, 0, (int32_t*)nullptr);
+                       0, mtiles, ntiles, (int64_t)0, 0, (int32_t*)nullptr, NextLayer{});
+    return hipGetLastError();
+}
+
+hipError_t launch_linear_e3m2_next(const uint8_t* act, const void* w_packed,
+                                   const float* h, const void* L2, const float* bias,
+                                   int64_t M, int N, int K, int r, bool gelu,
+                                   const float* next_inv_lambda, float next_rho, const void* next_l1p, int next_r,
+                                   uint8_t* next_act, float* next_sx, float* next_h, hipStream_t stream) {
+    const int mtiles = (int)((M + BM - 1) / BM), ntiles = N / BN;
+    const uint8_t* base = (const uint8_t*)w_packed;
+    const NextLayer nx{next_inv_lambda, (const uint4*)next_l1p, next_act, next_sx, next_h, next_rho, next_l1p ? next_r : 0};
+    if (nx.r > 0) {                                             // the tiles ADD their shares of h'
+        const int64_t n = M * next_r;
+        hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, stream, next_h, n);
+    }
+    auto kern = gelu ? gemm_e3m2_kernel<MODE_NEXT_GELU> : gemm_e3m2_kernel<MODE_NEXT>;
+    hipLaunchKernelGGL(kern, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
+                       act, base, base + w0_bytes(N, K), base + w0_bytes(N, K) + w1_bytes(N, K),
+                       h, (const uint16_t*)L2, bias, M, N, K, r, (void*)nullptr, (int64_t)0, 0,
+                       0, mtiles, ntiles, (int64_t)0, 0, (int32_t*)nullptr, nx);
     return hipGetLastError();
 }
 
@@ -456,11 +603,11 @@ hipError_t launch_group_acc_e3m2(const uint8_t* act, const void* w_packed, int64
     const int t0 = (int)(m0 / BM), t1 = (int)((m0 + mt + BM - 1) / BM);
     const int mtiles = t1 - t0, ntiles = N / BN;
     const uint8_t* base = (const uint8_t*)w_packed;
-    hipLaunchKernelGGL(gemm_e3m2_kernel<true>, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
+    hipLaunchKernelGGL(gemm_e3m2_kernel<MODE_DUMP>, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
                        act, base, base + w0_bytes(N, K), (const uint8_t*)nullptr,
                        (const float*)nullptr, (const uint16_t*)nullptr, (const float*)nullptr,
                        M, N, K, 0, (void*)nullptr, (int64_t)0, 0,
-                       t0, mtiles, ntiles, m0, mt, acc);
+                       t0, mtiles, ntiles, m0, mt, acc, NextLayer{});
     return hipGetLastError();
 }
 

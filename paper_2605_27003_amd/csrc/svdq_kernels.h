@@ -38,6 +38,11 @@ hipError_t launch_linear_e3m2(const uint8_t* act, const void* w_packed,
                               const float* h, const void* L2, const float* bias,
                               int64_t M, int N, int K, int r, void* y, int64_t ldy, int out_f32,
                               hipStream_t stream);
+hipError_t launch_linear_e3m2_next(const uint8_t* act, const void* w_packed,
+                                   const float* h, const void* L2, const float* bias,
+                                   int64_t M, int N, int K, int r, bool gelu,
+                                   const float* next_inv_lambda, float next_rho, const void* next_l1p, int next_r,
+                                   uint8_t* next_act, float* next_sx, float* next_h, hipStream_t stream);
 hipError_t launch_group_acc_e3m2(const uint8_t* act, const void* w_packed, int64_t M, int N, int K,
                                  int64_t m0, int mt, int32_t* acc, hipStream_t stream);
 hipError_t launch_unpack_act_e3m2(const uint8_t* act, int64_t M, int K, uint8_t* qx, hipStream_t stream);

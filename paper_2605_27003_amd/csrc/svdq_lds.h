@@ -89,8 +89,8 @@ __device__ __forceinline__ void store_tile_bf16(AccFn acc, uint32_t region, int 
         for (int mi = 0; mi < MT; ++mi)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const uint2 o = {f_bf16_rne(acc(ni, mi, 4 * q + 0)) | (f_bf16_rne(acc(ni, mi, 4 * q + 1)) << 16),
-                                 f_bf16_rne(acc(ni, mi, 4 * q + 2)) | (f_bf16_rne(acc(ni, mi, 4 * q + 3)) << 16)};
+                const uint2 o = {f2_bf16_rne(acc(ni, mi, 4 * q + 0), acc(ni, mi, 4 * q + 1)),
+                                 f2_bf16_rne(acc(ni, mi, 4 * q + 2), acc(ni, mi, 4 * q + 3))};
                 lds_write8_pinned(region + (mi * 32 + l32) * YROW + (ni * 32 + 8 * q + 4 * kh) * 2, o);
             }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

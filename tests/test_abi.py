@@ -96,6 +96,15 @@ def test_argument_errors_before_any_launch():
     assert g6(a, a, a, z, z, 4, 512, 512, 16, a, 512, 0, z) == INV            # h without L2
     assert g6(a, a, z, z, z, 4, 500, 512, 0, a, 512, 0, z) == SHAPE           # N % 128
     assert g6(a, a, z, z, z, 0, 512, 512, 0, a, 512, 0, z) == 0
+    gn = lib.svdq_linear_w4a4_e3m2_next                                         # two layers fused across their boundary
+    assert gn(a, a, z, z, z, 4, 512, 512, 0, 1, z, 0.9, z, 0, a, z, z, z) == INV      # no smoothing vector of the next layer
+    assert gn(a, a, z, z, z, 4, 512, 512, 0, 1, a, 0.9, z, 0, z, z, z, z) == INV      # no output buffer
+    assert gn(a, a, z, z, z, 4, 512, 512, 0, 1, a, 1.5, z, 0, a, z, z, z) == INV      # next rho > 1
+    assert gn(a, a, z, z, z, 4, 512, 512, 0, 1, a, 0.9, a, 16, a, z, z, z) == INV     # next L1 without next h
+    assert gn(a, a, z, z, z, 4, 512, 512, 0, 1, a, 0.9, z, 16, a, z, z, z) == INV     # next rank without next L1
+    assert gn(a, a, z, z, z, 4, 500, 512, 0, 1, a, 0.9, z, 0, a, z, z, z) == SHAPE
+    assert gn(a, a, z, z, z, 4, 512, 512, 0, 1, a, 0.9, a, 8, a, z, a, z) == SHAPE    # next rank 8
+    assert gn(a, a, z, z, z, 0, 512, 512, 0, 1, a, 0.9, z, 0, a, z, z, z) == 0
     assert lib.svdq_pack_weight_e3m2(z, a, 512, 512, a, z) == INV
     assert lib.svdq_pack_weight_e3m2(a, a, 512, 100, a, z) == SHAPE
     assert lib.svdq_unpack_act_e3m2(a, 4, 100, a, z) == SHAPE

@@ -1,0 +1,156 @@
+"""Two layers fused across their boundary (svdq_linear_w4a4_e3m2_next): the first layer's tile goes through bf16
+rounding, GELU and the second layer's quantise pass without y reaching memory.
+
+Three legs.  (1) Against the oracle, bit for bit, on inputs whose first-layer output is exactly representable in
+bf16 (small integer codes, power-of-two scales), so that the oracle's chain linear -> GELU -> quantise and the
+GPU's see the same activations.  (2) Against the oracle on the synthetic workload shapes: y of the two sides
+differs by one bf16 step in a few percent of the elements (the stated bar of y), so codes and scales are compared
+bit for bit on every (token, group) whose 64 activations agree, the rest must be within one code of the oracle
+after rescaling, and h' within a tolerance derived from those steps.  (3) Against the library's own un-fused
+sequence, which legs of other test files pin to the oracle piece by piece: identical bytes.
+"""
+import numpy as np
+import pytest
+import torch
+
+from workloads import synth
+from tests.helpers import DeviceLayer, dev, host_bits, pack_act_e3m2_np, rel_fro, unpack_act_e3m2_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def svdq():
+    import paper_2605_27003_amd as m
+    m.load_library(build_if_missing=False)
+    assert torch.cuda.is_available()
+    return m
+
+
+def next_layer(seed, K2, r2):
+    """Smoothing vector and L1 of a second layer whose K axis has K2 channels."""
+    cm = (np.abs(np.random.default_rng(seed).standard_normal(K2)) + 0.25).astype(np.float32)
+    return synth.make_layer(seed, K2, 128, r2, cm)
+
+
+def zeroed_out(svdq, M, N, r2):
+    act = svdq.ActE3M2(torch.zeros(svdq.act_e3m2_bytes(M, N), dtype=torch.uint8, device="cuda"), M, N)
+    sx = torch.zeros((N // 64, M), dtype=torch.float32, device="cuda")
+    h = torch.full((M, r2), 3.0, dtype=torch.float32, device="cuda") if r2 else None    # the call must clear it
+    return act, sx, h
+
+
+def test_exact_inputs_equal_oracle_chain(svdq, oracle):
+    M, K, N, r, r2 = 203, 128, 256, 16, 32
+    g = np.random.default_rng(41)
+    cx = g.integers(-1, 2, (M, K))
+    cw = g.integers(-1, 2, (N, K))
+    qx, qw = synth.pack_int4(cx), synth.pack_int4(cw)
+    sx = np.ones((M, K // 64), np.float32)
+    sw = np.full((K // 64, N), 0.25, np.float32)
+    h = g.integers(-1, 2, (M, r)).astype(np.float32)
+    L2 = synth.to_bf16_bits((g.integers(-1, 2, (r, N)) * 0.25).astype(np.float32))
+    bias = (g.integers(-4, 5, N) * 0.25).astype(np.float32)
+    orc = oracle.linear(qx, sx, qw, sw, h.astype(np.float64), L2, bias)
+    y = orc["y64"]
+    assert np.array_equal(synth.bf16_bits_to_f32(orc["ybf16"]).astype(np.float64), y) and np.abs(y).max() > 4
+    L = next_layer(3, N, r2)
+    for gelu in (True, False):
+        xg = oracle.gelu_tanh_bf16(orc["ybf16"]) if gelu else orc["ybf16"]
+        oq, os_ = oracle.quantize_act(xg, L.inv_lambda, 0.75)
+        oh = oracle.lowrank_down(xg, L.inv_lambda, L.L1)
+        il = dev(L.inv_lambda)
+        act = svdq.ActE3M2(dev(pack_act_e3m2_np(cx, sx)), M, K)
+        wp = svdq.pack_weight_e3m2(dev(qw), dev(sw))
+        out = zeroed_out(svdq, M, N, r2)
+        nact, nsx, nh = svdq.linear_w4a4_e3m2_next(act, wp, N, il, 0.75, dev(h), dev(L2), dev(bias), gelu=gelu,
+                                                   next_l1_packed=svdq.pack_lowrank_down(dev(L.L1), il), next_r=r2,
+                                                   out=out)
+        torch.cuda.synchronize()
+        codes, pieces = unpack_act_e3m2_np(nact.buf.cpu().numpy(), M, N)
+        assert np.array_equal(codes, synth.unpack_int4(oq)), gelu
+        assert np.array_equal(nsx.cpu().numpy().T.view(np.uint32), os_.view(np.uint32)), gelu
+        hi = synth.to_bf16_bits(os_)
+        lo = synth.to_bf16_bits((os_ - synth.bf16_bits_to_f32(hi)).astype(np.float32))
+        assert np.array_equal(pieces, hi.astype(np.uint32) | (lo.astype(np.uint32) << 16))
+        assert rel_fro(nh.cpu().numpy(), oh) <= 3e-5, gelu
+
+
+CHAIN = [(333, 256, 256, 32, 32, True), (130, 192, 128, 16, 16, False), (1, 64, 128, 0, 0, True),
+         (700, 1024, 1536, 32, 32, True), (257, 320, 384, 32, 0, True)]
+
+
+@pytest.mark.parametrize("M,K,N,r,r2,gelu", CHAIN)
+def test_chain_against_oracle_and_unfused(svdq, oracle, M, K, N, r, r2, gelu):
+    x, cm = synth.make_x(50 + M, M, K, outlier_count=3, outlier_scale=30.0)
+    L1 = synth.make_layer(50 + M, K, N, r, cm)
+    # the up-projection's output feeds a GELU: give it the spread of a pre-activation (about N(0, 1.5^2))
+    L1.sw = (L1.sw * np.float32(6.0)).astype(np.float32)
+    L2 = next_layer(9, N, r2)
+    D1 = DeviceLayer(L1)
+    il2 = dev(L2.inv_lambda)
+    l1p2 = svdq.pack_lowrank_down(dev(L2.L1), il2) if r2 else None
+    rho1, rho2 = 0.9, 0.8
+    act, _, h = svdq.quantize_act_e3m2(dev(x), D1.inv_lambda, rho1, D1.l1p, r, want_sx=False)
+
+    # (3) un-fused sequence of the same library: identical bytes, h' up to summation order
+    y = svdq.linear_w4a4_e3m2(act, D1.wp6, N, h, D1.L2, D1.bias)
+    ref = zeroed_out(svdq, M, N, r2)
+    if gelu:
+        svdq.quantize_act_gelu(svdq.FMT_INT4_E3M2, y, il2, rho2, l1p2, r2, out=ref)
+    else:
+        svdq.quantize_act_e3m2(y, il2, rho2, l1p2, r2, out=ref)
+    out = zeroed_out(svdq, M, N, r2)
+    nact, nsx, nh = svdq.linear_w4a4_e3m2_next(act, D1.wp6, N, il2, rho2, h, D1.L2, D1.bias, gelu=gelu,
+                                               next_l1_packed=l1p2, next_r=r2, out=out)
+    torch.cuda.synchronize()
+    assert torch.equal(nact.buf, ref[0].buf) and torch.equal(nsx, ref[1])
+    if r2:
+        hr = ref[2].double()
+        assert float((nh.double() - hr).norm() / hr.norm()) <= 1e-6
+
+    # (2) the oracle's chain
+    oq, os_ = oracle.quantize_act(x, L1.inv_lambda, rho1)
+    oh = oracle.lowrank_down(x, L1.inv_lambda, L1.L1) if r else None
+    orc = oracle.linear(oq, os_, L1.qw, L1.sw, oh, L1.L2 if r else None, L1.bias)
+    xg = oracle.gelu_tanh_bf16(orc["ybf16"]) if gelu else orc["ybf16"]
+    oq2, os2 = oracle.quantize_act(xg, L2.inv_lambda, rho2)
+    oc2 = synth.unpack_int4(oq2)
+    same = (host_bits(y) == orc["ybf16"]).reshape(M, N // 64, 64).all(axis=2)       # [M, N/64]
+    if same.size >= 200:
+        assert same.mean() > 0.03, same.mean()                                      # the comparison is not vacuous
+    codes, _ = unpack_act_e3m2_np(nact.buf.cpu().numpy(), M, N)
+    gs = nsx.cpu().numpy().T
+    assert np.array_equal(gs.view(np.uint32)[same], os2.view(np.uint32)[same])
+    assert np.array_equal(codes.reshape(M, -1, 64)[same], oc2.reshape(M, -1, 64)[same])
+    # elsewhere: one bf16 step of y is at most two steps of the activated value (2^-6 relative), which moves a
+    # scale by at most that and a code (|x^ / s| <= 8) by at most one: |q' s' - q s| <= s (1 + 2^-6) + 8 s 2^-6
+    live = os2 > 0
+    assert np.all(np.abs(gs[live] / os2[live] - 1) <= 1.01 * 2.0 ** -6)
+    dq = codes.reshape(M, -1, 64) * gs[:, :, None]
+    do = oc2.reshape(M, -1, 64) * os2[:, :, None]
+    assert np.all(np.abs(dq - do) <= 1.15 * os2[:, :, None] + 1e-30)
+    assert np.mean(codes != oc2) < 0.05
+    if r2:
+        oh2 = oracle.lowrank_down(xg, L2.inv_lambda, L2.L1)
+        assert rel_fro(nh.cpu().numpy(), oh2) <= 3e-3
+
+
+def test_argument_errors(svdq):
+    lib = svdq.load_library()
+    a = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda").data_ptr()
+    INV, SHAPE = -1, -2
+    ok = [a, a, a, a, a, 4, 128, 64, 16, 1, a, 0.9, a, 16, a, a, a, None]
+    assert lib.svdq_linear_w4a4_e3m2_next(*ok) == 0
+
+    def bad(i, v):
+        args = list(ok)
+        args[i] = v
+        return lib.svdq_linear_w4a4_e3m2_next(*args)
+
+    assert bad(0, None) == INV and bad(10, None) == INV and bad(14, None) == INV
+    assert bad(11, 0.0) == INV and bad(11, 1.5) == INV and bad(11, float("nan")) == INV
+    assert bad(16, None) == INV                                  # L1' without h'
+    assert bad(6, 192) == SHAPE and bad(7, 100) == SHAPE and bad(13, 8) == SHAPE and bad(8, 8) == SHAPE
+    assert bad(10, a + 4) == SHAPE
+    assert bad(5, 0) == 0 and bad(15, None) == 0                 # empty batch; sx is optional
