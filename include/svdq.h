@@ -293,6 +293,19 @@ int svdq_linear_mxfp4(const uint8_t* qx, const uint8_t* sx_e8m0, const void* w_p
                       int64_t M, int N, int K, int r,
                       void* y, int64_t ldy, int out_dtype, void* stream);
 
+/* svdq_linear_w4a4_e3m2_next for the MXFP4 layer: svdq_linear_mxfp4 whose epilogue rounds each tile to
+ * bf16, applies GELU if `gelu` != 0 and writes what svdq_quantize_act_mxfp4 (svdq_quantize_act_gelu
+ * with SVDQ_FMT_MXFP4) of that output would write for the next layer (K' = N): next_qx
+ * [N/64][M][32 B] and next_sx_e8m0 [N/128][M][2][2] bit for bit, next_h [M, next_r] (zeroed by the
+ * call, then accumulated with atomic adds: last bits vary with summation order).  next_* as for
+ * svdq_linear_w4a4_e3m2_next; shapes and errors as svdq_linear_mxfp4. */
+int svdq_linear_mxfp4_next(const uint8_t* qx, const uint8_t* sx_e8m0, const void* w_packed,
+                           const float* h, const void* L2_bf16, const float* bias,
+                           int64_t M, int N, int K, int r, int gelu,
+                           const float* next_inv_lambda, float next_rho,
+                           const void* next_l1_packed, int next_r,
+                           uint8_t* next_qx, uint8_t* next_sx_e8m0, float* next_h, void* stream);
+
 /*
  * Offline calibration, Sec. III-C: the clipping ratio of a (layer, timestep bin) is the candidate that
  * minimises the expected squared reconstruction error || Y - Y^(rho) ||^2 of the quantised layer over

@@ -38,6 +38,8 @@ EXPORTS = {
     "svdq_packed_weight_mxfp4_bytes": (ctypes.c_size_t, [_i32, _i32]),
     "svdq_pack_weight_mxfp4": (_i32, [_vp, _vp, _i32, _i32, _vp, _vp]),
     "svdq_linear_mxfp4": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _i32, _vp]),
+    "svdq_linear_mxfp4_next": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _i32,
+                                      _vp, _f32, _vp, _i32, _vp, _vp, _vp, _vp]),
     "svdq_gptq_workspace_bytes": (ctypes.c_size_t, [_i32, _i32]),
     "svdq_gptq_hessian": (_i32, [_vp, _i64, _vp, _i64, _i32, _vp, _vp]),
     "svdq_gptq_quantize": (_i32, [_vp, _vp, ctypes.c_double, _i32, _i32, _vp, _vp, _vp, _vp]),
@@ -398,6 +400,27 @@ def linear_mxfp4(qx, sx, w_packed, N, h=None, L2_bf16=None, bias=None, out=None,
     _check(load_library().svdq_linear_mxfp4(_ptr(qx), _ptr(sx), _ptr(w_packed), _ptr(h), _ptr(L2_bf16), _ptr(bias),
                                             M, N, K, r, _ptr(out), ldy, code, _stream()), "svdq_linear_mxfp4")
     return out
+
+
+def linear_mxfp4_next(qx, sx, w_packed, N, next_inv_lambda, next_rho, h=None, L2_bf16=None, bias=None, gelu=True,
+                      next_l1_packed=None, next_r=0, out=None):
+    """The MXFP4 layer fused with the NEXT layer's quantise pass (optionally through GELU): returns what
+    quantize_act_mxfp4 / quantize_act_gelu(FMT_MXFP4) of this layer's bf16 output would return
+    (qx' [N/64,M,32], sx' [N/128,M,2,2], h' [M,next_r] or None), without y ever being stored."""
+    ng, M, _ = qx.shape
+    K = 64 * ng
+    r = 0 if h is None else h.shape[1]
+    if out is None:
+        nq = torch.empty((N // 64, M, 32), dtype=torch.uint8, device=qx.device)
+        ns = torch.empty((N // 128, M, 2, 2), dtype=torch.uint8, device=qx.device)
+        nh = torch.empty((M, next_r), dtype=torch.float32, device=qx.device) if next_l1_packed is not None else None
+    else:
+        nq, ns, nh = out
+    _check(load_library().svdq_linear_mxfp4_next(
+        _ptr(qx), _ptr(sx), _ptr(w_packed), _ptr(h), _ptr(L2_bf16), _ptr(bias), M, N, K, r, int(bool(gelu)),
+        _ptr(next_inv_lambda), float(next_rho), _ptr(next_l1_packed), next_r if next_l1_packed is not None else 0,
+        _ptr(nq), _ptr(ns), _ptr(nh), _stream()), "svdq_linear_mxfp4_next")
+    return nq, ns, nh
 
 
 # ---- clipping-ratio search (offline calibration, Sec. III-C) ---------------------------------

@@ -332,6 +332,29 @@ int svdq_linear_mxfp4(const uint8_t* qx, const uint8_t* sx_e8m0, const void* w_p
                                              out_dtype == SVDQ_OUT_F32, (hipStream_t)stream));
 }
 
+int svdq_linear_mxfp4_next(const uint8_t* qx, const uint8_t* sx_e8m0, const void* w_packed,
+                           const float* h, const void* L2_bf16, const float* bias,
+                           int64_t M, int N, int K, int r, int gelu,
+                           const float* next_inv_lambda, float next_rho,
+                           const void* next_l1_packed, int next_r,
+                           uint8_t* next_qx, uint8_t* next_sx_e8m0, float* next_h, void* stream) {
+    if (!qx || !sx_e8m0 || !w_packed || !next_inv_lambda || !next_qx || !next_sx_e8m0 || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (r == 0 ? (h || L2_bf16) : (!h || !L2_bf16)) return SVDQ_ERR_INVALID_ARG;
+    if (!(next_rho > 0.0f) || !(next_rho <= 1.0f)) return SVDQ_ERR_INVALID_ARG;
+    if (next_l1_packed ? (!next_h) : (next_r != 0)) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if ((r != 0 && !rank_ok(r)) || (next_l1_packed && !rank_ok(next_r))) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(qx) || !aligned16(sx_e8m0) || !aligned16(w_packed) || !aligned16(h) || !aligned16(L2_bf16) ||
+        !aligned16(bias) || !aligned16(next_inv_lambda) || !aligned16(next_l1_packed) || !aligned16(next_qx) ||
+        !aligned16(next_sx_e8m0) || (next_l1_packed && !aligned16(next_h)))
+        return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_linear_mx_next(qx, sx_e8m0, w_packed, h, L2_bf16, bias, M, N, K, r, gelu != 0,
+                                                  next_inv_lambda, next_rho, next_l1_packed, next_r,
+                                                  next_qx, next_sx_e8m0, next_h, (hipStream_t)stream));
+}
+
 size_t svdq_gptq_workspace_bytes(int N, int K) {
     if (N <= 0 || K <= 0 || K % SVDQ_GROUP) return 0;
     return svdq::gptq_workspace_bytes(N, K);

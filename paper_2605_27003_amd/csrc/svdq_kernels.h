@@ -57,6 +57,11 @@ hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w
                             const float* h, const void* L2, const float* bias,
                             int64_t M, int N, int K, int r, void* y, int64_t ldy, int out_f32,
                             hipStream_t stream);
+hipError_t launch_linear_mx_next(const uint8_t* qx, const uint8_t* sxe, const void* w_packed,
+                                 const float* h, const void* L2, const float* bias,
+                                 int64_t M, int N, int K, int r, bool gelu,
+                                 const float* next_inv_lambda, float next_rho, const void* next_l1p, int next_r,
+                                 uint8_t* next_qx, uint8_t* next_sxe, float* next_h, hipStream_t stream);
 
 // svdq_search.hip
 constexpr int SQ_ERROR_PARTIALS = 1024;

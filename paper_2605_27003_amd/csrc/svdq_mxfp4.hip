@@ -277,13 +277,31 @@ struct MxGeom {
     static_assert(WNC == 2 || (WNC == 4 && MT == 4), "staging is written for 4 waves, or 8 waves with 256 tokens");
 };
 
-template <int MT, int WNC>
+// MODE: MX_LAYER stores y.  MX_NEXT / MX_NEXT_GELU (four-wave geometry only): y never reaches HBM; the wave rounds
+// its tile to bf16, optionally applies GELU and runs the NEXT layer's kernel (a') on it.  A wave's 64 channels are two
+// MX blocks of the next layer's K axis: after lanes l and l + 32 have traded n-blocks a lane holds one whole block
+// of its token, so the shared exponent and the codes need no further exchange; the wave's share of
+// h' = x^' L1' is added to the zeroed h' with atomic adds (after the two waves that share tokens have been summed
+// in LDS).
+enum { MX_LAYER = 0, MX_NEXT = 1, MX_NEXT_GELU = 2 };
+struct MxNext {
+    const float* inv_lambda;     // [N]
+    const uint4* l1p;            // packed L1' (K' = N) or null
+    uint8_t* qx;                 // [N/64][M][32 B]
+    uint8_t* sxe;                // [N/128][M][2][2]
+    float* h;                    // [M, r]
+    float rho;
+    int r;
+};
+
+template <int MT, int WNC, int MODE>
 __global__ __launch_bounds__(128 * WNC, (WNC == 2) ? 2 : 1)
 void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__ sxe,
                     const uint4* __restrict__ wfrag, const uint16_t* __restrict__ wscale,
                     const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
                     int64_t M, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
-                    int mtiles, int ntiles) {
+                    int mtiles, int ntiles, const MxNext nx) {
+    static_assert(MODE == MX_LAYER || WNC == 2, "the emitting epilogue is written for the four-wave geometry");
     using G = MxGeom<MT, WNC>;
     constexpr int BM = G::BM;
     constexpr int NDMA = G::NDMA;
@@ -465,6 +483,91 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     // ---- epilogue (c): low-rank up-projection on the bf16 matrix cores, bias, store
     const int64_t mw = m0 + wm * (32 * MT);                   // first token of this wave's tile
     add_lowrank_bias<2, MT>(y, h, L2, bias, mw, n0 + wn * 64, M, N, r, lane);
+    if constexpr (MODE != MX_LAYER) {
+        const int gq = (n0 + wn * 64) >> 6;                    // this wave's 64-group of the next layer (stage nt, slot wn)
+        const float* il = nx.inv_lambda + n0 + wn * 64 + kh * 32;
+        uint4 bfrag[4][2];
+        if (nx.r > 0) {
+            const uint4* pb = nx.l1p + (size_t)gq * (4 * 2 * 64) + lane;
+#pragma unroll
+            for (int sI = 0; sI < 4; ++sI) {
+                bfrag[sI][0] = pb[(sI * 2 + 0) * 64];
+                bfrag[sI][1] = pb[(sI * 2 + 1) * 64];
+            }
+        }
+        float16v hp[MT];
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi) {
+            // register 4 q + j of y[ni][mi] is channel 32 ni + 8 q + 4 kh + j of token mw + 32 mi + l32
+            uint32_t pk[2][8];
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int d = 0; d < 8; ++d) {
+                    uint32_t w = f2_bf16_rne(y[ni][mi][2 * d], y[ni][mi][2 * d + 1]);
+                    if (MODE == MX_NEXT_GELU) w = gelu_tanh_bf16x2(w);
+                    pk[ni][d] = w;
+                }
+            uint4 xc[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                // first result: own value in lanes 0..31, the lower lanes' second operand in lanes 32..63;
+                // second result: the upper lanes' first operand in lanes 0..31, own value in lanes 32..63
+                const auto e0 = __builtin_amdgcn_permlane32_swap(pk[0][2 * q], pk[1][2 * q], false, false);
+                const auto e1 = __builtin_amdgcn_permlane32_swap(pk[0][2 * q + 1], pk[1][2 * q + 1], false, false);
+                xc[q] = uint4{e0[0], e1[0], e0[1], e1[1]};     // channels 32 kh + 8 q + 0..7: MX block 2 gq + kh
+            }
+            uint4 codes;
+            uint32_t e8;
+            quantize_block_mx(xc, il, nx.rho, codes, e8);
+            const int64_t row = mw + mi * 32 + l32;
+            if (row < M) {
+                *reinterpret_cast<uint4*>(nx.qx + ((size_t)gq * M + row) * 32 + kh * 16) = codes;
+                nx.sxe[(((size_t)(gq >> 1) * M + row) * 2 + kh) * 2 + (gq & 1)] = (uint8_t)e8;
+            }
+            if (nx.r > 0) {
+                float16v acc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+#pragma unroll
+                for (int sI = 0; sI < 4; ++sI) {
+                    const bf16x8 av = __builtin_bit_cast(bf16x8, xc[sI]);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sI][0]), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sI][1]), acc, 0, 0, 0);
+                }
+                hp[mi] = acc;                                  // [token][j]: lane holds column j = l32
+            }
+        }
+        if (nx.r > 0) {
+            __syncthreads();                                   // every wave is done with the operand ring
+            float* part = reinterpret_cast<float*>(ring) + wm * (MT * 16 * 64) + lane;
+            if (wn == 1) {
+#pragma unroll
+                for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) part[(mi * 16 + i) * 64] = hp[mi][i];
+            }
+            __syncthreads();
+            if (wn == 0) {
+#pragma unroll
+                for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) hp[mi][i] += part[(mi * 16 + i) * 64];
+                // register (mi, i) is token mw + 4 kh + [32 mi + 8 (i / 4) + i % 4] of column l32
+                const int64_t first = mw + 4 * kh;
+                const int left = (l32 < nx.r && first < M) ? (int)((M - first < 32 * MT) ? M - first : 32 * MT) : 0;
+                float* hb = nx.h + first * nx.r + l32;
+#pragma unroll
+                for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int rl = 32 * mi + 8 * (i >> 2) + (i & 3);
+                        if (rl < left) unsafeAtomicAdd(hb + rl * nx.r, hp[mi][i]);
+                    }
+            }
+        }
+        return;
+    }
     if (out_f32) {
         store_tile_f32<2, MT>(y, reinterpret_cast<float*>(yout), ldy, mw, n0 + wn * 64, M, lane);
     } else {
@@ -526,15 +629,44 @@ hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w
     const int sms = (mtiles + 63) / 64;
     if (N % 256 == 0) {                      // 256 x 256 block tiles, eight waves, one block per CU
         const int ntiles = N / 256;
-        hipLaunchKernelGGL((gemm_mx_kernel<MT, 4>), dim3((unsigned)(sms * 64 * ntiles)), dim3(512), 0, stream,
+        hipLaunchKernelGGL((gemm_mx_kernel<MT, 4, MX_LAYER>), dim3((unsigned)(sms * 64 * ntiles)), dim3(512), 0, stream,
                            qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
-                           M, N, K, r, y, ldy, out_f32, mtiles, ntiles);
+                           M, N, K, r, y, ldy, out_f32, mtiles, ntiles, MxNext{});
     } else {                                 // 256 x 128 block tiles, four waves, two blocks per CU
         const int ntiles = N / 128;
-        hipLaunchKernelGGL((gemm_mx_kernel<MT, 2>), dim3((unsigned)(sms * 64 * ntiles)), dim3(256), 0, stream,
+        hipLaunchKernelGGL((gemm_mx_kernel<MT, 2, MX_LAYER>), dim3((unsigned)(sms * 64 * ntiles)), dim3(256), 0, stream,
                            qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
-                           M, N, K, r, y, ldy, out_f32, mtiles, ntiles);
+                           M, N, K, r, y, ldy, out_f32, mtiles, ntiles, MxNext{});
     }
+    return hipGetLastError();
+}
+
+__global__ void zero_f32_mx_kernel(float* __restrict__ p, int64_t n) {   // a kernel, not a memset (graph replays)
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i + 4 <= n) *reinterpret_cast<float4*>(p + i) = float4{0.f, 0.f, 0.f, 0.f};
+    else for (int64_t j = i; j < n; ++j) p[j] = 0.f;
+}
+
+hipError_t launch_linear_mx_next(const uint8_t* qx, const uint8_t* sxe, const void* w_packed,
+                                 const float* h, const void* L2, const float* bias,
+                                 int64_t M, int N, int K, int r, bool gelu,
+                                 const float* next_inv_lambda, float next_rho, const void* next_l1p, int next_r,
+                                 uint8_t* next_qx, uint8_t* next_sxe, float* next_h, hipStream_t stream) {
+    constexpr int MT = 4;
+    const uint8_t* base = (const uint8_t*)w_packed;
+    const uint16_t* wsc = (const uint16_t*)(base + mx_wfrag_bytes(N, K));
+    const int mtiles = (int)((M + 64 * MT - 1) / (64 * MT));
+    const int sms = (mtiles + 63) / 64;
+    const int ntiles = N / 128;
+    const MxNext nx{next_inv_lambda, (const uint4*)next_l1p, next_qx, next_sxe, next_h, next_rho, next_l1p ? next_r : 0};
+    if (nx.r > 0) {                                             // the tiles ADD their shares of h'
+        const int64_t n = M * next_r;
+        hipLaunchKernelGGL(zero_f32_mx_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, stream, next_h, n);
+    }
+    auto kern = gelu ? gemm_mx_kernel<MT, 2, MX_NEXT_GELU> : gemm_mx_kernel<MT, 2, MX_NEXT>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(sms * 64 * ntiles)), dim3(256), 0, stream,
+                       qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
+                       M, N, K, r, (void*)nullptr, (int64_t)0, 0, mtiles, ntiles, nx);
     return hipGetLastError();
 }
 

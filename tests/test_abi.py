@@ -80,6 +80,11 @@ def test_argument_errors_before_any_launch():
     assert gm(a, a, a, a, z, z, 4, 512, 512, 16, a, 512, 0, z) == INV         # h without L2
     assert gm(a, a, a, z, z, z, 4, 500, 512, 0, a, 512, 0, z) == SHAPE        # N % 128
     assert gm(a, a, a, z, z, z, 0, 512, 512, 0, a, 512, 0, z) == 0
+    gmn = lib.svdq_linear_mxfp4_next
+    assert gmn(a, a, a, z, z, z, 4, 512, 512, 0, 1, a, 0.9, z, 0, a, z, z, z) == INV      # no scale output
+    assert gmn(a, a, a, z, z, z, 4, 512, 512, 0, 1, a, 0.9, a, 16, a, a, z, z) == INV     # next L1 without next h
+    assert gmn(a, a, a, z, z, z, 4, 500, 512, 0, 1, a, 0.9, z, 0, a, a, z, z) == SHAPE
+    assert gmn(a, a, a, z, z, z, 0, 512, 512, 0, 1, a, 0.9, z, 0, a, a, z, z) == 0
     assert lib.svdq_pack_weight_mxfp4(z, a, 512, 512, a, z) == INV
     assert lib.svdq_pack_weight_mxfp4(a, a, 512, 100, a, z) == SHAPE
     assert svdq.packed_weight_mxfp4_bytes(5120, 5120) >= 5120 * 2560 and svdq.packed_weight_mxfp4_bytes(100, 5120) == 0

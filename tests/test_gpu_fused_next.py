@@ -154,3 +154,121 @@ def test_argument_errors(svdq):
     assert bad(6, 192) == SHAPE and bad(7, 100) == SHAPE and bad(13, 8) == SHAPE and bad(8, 8) == SHAPE
     assert bad(10, a + 4) == SHAPE
     assert bad(5, 0) == 0 and bad(15, None) == 0                 # empty batch; sx is optional
+
+
+# ------------------------------------------------------------------------------------------------ MXFP4
+def mx_group_major(qx_tm, sx_tm):
+    """Token-major MXFP4 activations (qx [M,K/2], sx [M,K/32]; K a multiple of 128) -> the layout of the C ABI:
+    qx [K/64][M][32], sx [K/128][M][half][group-in-stage]."""
+    M, K2 = qx_tm.shape
+    ng = K2 // 32
+    q = np.ascontiguousarray(qx_tm.reshape(M, ng, 32).transpose(1, 0, 2))
+    s = np.ascontiguousarray(sx_tm.reshape(M, ng // 2, 2, 2).transpose(1, 0, 3, 2))     # [s][m][h][j] <- [m][s][j][h]
+    return q, s
+
+
+def mx_zeroed_out(M, N, r2):
+    q = torch.zeros((N // 64, M, 32), dtype=torch.uint8, device="cuda")
+    s = torch.zeros((N // 128, M, 2, 2), dtype=torch.uint8, device="cuda")
+    h = torch.full((M, r2), 3.0, dtype=torch.float32, device="cuda") if r2 else None
+    return q, s, h
+
+
+def test_mx_exact_inputs_equal_oracle_chain(svdq, oracle):
+    M, K, N, r, r2 = 203, 128, 256, 16, 32
+    g = np.random.default_rng(43)
+    e2m1 = np.array([0xA, 0x0, 0x2], np.uint8)                       # E2M1 codes of -1, 0, +1
+    cx, cw = g.integers(0, 3, (M, K)), g.integers(0, 3, (N, K))
+    qx = (e2m1[cx[:, 0::2]] | (e2m1[cx[:, 1::2]] << 4)).astype(np.uint8)
+    qw = (e2m1[cw[:, 0::2]] | (e2m1[cw[:, 1::2]] << 4)).astype(np.uint8)
+    sx = np.full((M, K // 32), 127, np.uint8)                        # 2^0
+    sw = np.full((K // 32, N), 125, np.uint8)                        # 2^-2
+    h = g.integers(-1, 2, (M, r)).astype(np.float32)
+    L2 = synth.to_bf16_bits((g.integers(-1, 2, (r, N)) * 0.25).astype(np.float32))
+    bias = (g.integers(-4, 5, N) * 0.25).astype(np.float32)
+    orc = oracle.linear_mxfp4(qx, sx, qw, sw, h.astype(np.float64), L2, bias)
+    y = orc["y64"]
+    assert np.array_equal(synth.bf16_bits_to_f32(orc["ybf16"]).astype(np.float64), y) and np.abs(y).max() > 4
+    L = next_layer(3, N, r2)
+    il = dev(L.inv_lambda)
+    qg, sg = mx_group_major(qx, sx)
+    wp = svdq.pack_weight_mxfp4(dev(qw), dev(sw))
+    for gelu in (True, False):
+        xg = oracle.gelu_tanh_bf16(orc["ybf16"]) if gelu else orc["ybf16"]
+        oq, os_ = oracle.quantize_act_mxfp4(xg, L.inv_lambda, 0.75)
+        oh = oracle.lowrank_down(xg, L.inv_lambda, L.L1)
+        nq, ns, nh = svdq.linear_mxfp4_next(dev(qg), dev(sg), wp, N, il, 0.75, dev(h), dev(L2), dev(bias), gelu=gelu,
+                                            next_l1_packed=svdq.pack_lowrank_down(dev(L.L1), il), next_r=r2,
+                                            out=mx_zeroed_out(M, N, r2))
+        torch.cuda.synchronize()
+        gq, gs = svdq.mx_to_token_major(nq, ns, N)
+        assert np.array_equal(gs.cpu().numpy(), os_), gelu
+        assert np.array_equal(gq.cpu().numpy(), oq), gelu
+        assert rel_fro(nh.cpu().numpy(), oh) <= 3e-5, gelu
+
+
+@pytest.mark.parametrize("M,K,N,r,r2,gelu", CHAIN)
+def test_mx_chain_against_oracle_and_unfused(svdq, oracle, M, K, N, r, r2, gelu):
+    x, cm = synth.make_x(50 + M, M, K, outlier_count=3, outlier_scale=30.0)
+    L1 = synth.make_layer(50 + M, K, N, r, cm, fmt="mxfp4")
+    L1.sw = (L1.sw + 3).astype(np.uint8)                              # x 8: the spread of a pre-activation
+    L2 = next_layer(9, N, r2)
+    il1, il2 = dev(L1.inv_lambda), dev(L2.inv_lambda)
+    l1p1 = svdq.pack_lowrank_down(dev(L1.L1), il1) if r else None
+    l1p2 = svdq.pack_lowrank_down(dev(L2.L1), il2) if r2 else None
+    wp = svdq.pack_weight_mxfp4(dev(L1.qw), dev(L1.sw))
+    dL2, dbias = (dev(L1.L2) if r else None), dev(L1.bias)
+    rho1, rho2 = 0.9, 0.8
+    qx, sx, h = svdq.quantize_act_mxfp4(dev(x), il1, rho1, l1p1, r)
+
+    # un-fused sequence of the same library: identical bytes, h' up to summation order
+    y = svdq.linear_mxfp4(qx, sx, wp, N, h, dL2, dbias)
+    ref = mx_zeroed_out(M, N, r2)
+    if gelu:
+        svdq.quantize_act_gelu(svdq.FMT_MXFP4, y, il2, rho2, l1p2, r2, out=ref)
+    else:
+        svdq.quantize_act_mxfp4(y, il2, rho2, l1p2, r2, out=ref)
+    nq, ns, nh = svdq.linear_mxfp4_next(qx, sx, wp, N, il2, rho2, h, dL2, dbias, gelu=gelu,
+                                        next_l1_packed=l1p2, next_r=r2, out=mx_zeroed_out(M, N, r2))
+    torch.cuda.synchronize()
+    assert torch.equal(nq, ref[0]) and torch.equal(ns, ref[1])
+    if r2:
+        hr = ref[2].double()
+        assert float((nh.double() - hr).norm() / hr.norm()) <= 1e-6
+
+    # the oracle's chain: bit-exact on every (token, 32-block) whose activations agree
+    oq, os_ = oracle.quantize_act_mxfp4(x, L1.inv_lambda, rho1)
+    oh = oracle.lowrank_down(x, L1.inv_lambda, L1.L1) if r else None
+    orc = oracle.linear_mxfp4(oq, os_, L1.qw, L1.sw, oh, L1.L2 if r else None, L1.bias)
+    xg = oracle.gelu_tanh_bf16(orc["ybf16"]) if gelu else orc["ybf16"]
+    oq2, os2 = oracle.quantize_act_mxfp4(xg, L2.inv_lambda, rho2)
+    same = (host_bits(y) == orc["ybf16"]).reshape(M, N // 32, 32).all(axis=2)       # [M, N/32]
+    if same.size >= 400:
+        assert same.mean() > 0.1, same.mean()
+    gq, gs = svdq.mx_to_token_major(nq, ns, N)
+    gq, gs = gq.cpu().numpy(), gs.cpu().numpy()
+    assert np.array_equal(gs[same], os2[same])
+    assert np.array_equal(gq.reshape(M, -1, 16)[same], oq2.reshape(M, -1, 16)[same])
+    assert np.all(np.abs(gs.astype(int) - os2.astype(int)) <= 1)                    # a step of y moves an exponent by <= 1
+    assert np.mean(gq != oq2) < 0.05
+    if r2:
+        oh2 = oracle.lowrank_down(xg, L2.inv_lambda, L2.L1)
+        assert rel_fro(nh.cpu().numpy(), oh2) <= 3e-3
+
+
+def test_mx_argument_errors(svdq):
+    lib = svdq.load_library()
+    a = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda").data_ptr()
+    INV, SHAPE = -1, -2
+    ok = [a, a, a, a, a, a, 4, 128, 128, 16, 1, a, 0.9, a, 16, a, a, a, None]
+    assert lib.svdq_linear_mxfp4_next(*ok) == 0
+
+    def bad(i, v):
+        args = list(ok)
+        args[i] = v
+        return lib.svdq_linear_mxfp4_next(*args)
+
+    assert bad(0, None) == INV and bad(1, None) == INV and bad(11, None) == INV and bad(15, None) == INV
+    assert bad(16, None) == INV and bad(17, None) == INV and bad(12, 0.0) == INV and bad(12, float("nan")) == INV
+    assert bad(7, 192) == SHAPE and bad(8, 100) == SHAPE and bad(14, 8) == SHAPE and bad(11, a + 4) == SHAPE
+    assert bad(6, 0) == 0
