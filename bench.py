@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--workload", type=int, default=1, help="index into the five configurations (default: the metric's)")
     ap.add_argument("--cpu-rows", type=int, default=12288, help="token rows of the CPU-oracle baseline sample (0 = skip)")
     ap.add_argument("--skip-mxfp4", action="store_true", help="do not also time the MXFP4 variant of the layer")
+    ap.add_argument("--ffn-chain", action="store_true",
+                    help="also time the feed-forward chain up-projection -> GELU -> down-projection, un-fused (three "
+                         "kernels) and with the GEMM epilogue that emits the next layer's operands (two kernels)")
     ap.add_argument("--xsets", type=int, default=3, help="input buffer sets rotated so caches cannot hold the working set")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -229,6 +232,68 @@ def main():
         bytes_q = sum(M * (2 * rec["L"].K + rec["L"].K // 2 + sb(rec["L"].K) + 4 * rec["L"].r) for rec in per_expert[w.experts[0]])
         return dict(w=w, M=M, ms_step=(t1 - t0) * 1e3 / args.steps, tq=tq, tg=tg, ops=ops, bytes_q=bytes_q, nl=nl)
 
+    def ffn_chain(fmt):
+        """Up-projection (workload 3's layer and input) -> GELU -> quantise -> down-projection (workload 4's layer),
+        as three kernels and as two (the up-projection's epilogue emits the down-projection's operands)."""
+        f = "mxfp4" if fmt == "mxfp4" else "int4"
+        wu, wd = synth.workload(2, fmt=f), synth.workload(3, fmt=f)
+        Lu, Ld = wu.layers["e0/lin"], wd.layers["e0/lin"]
+        M, D, F, r = wu.M, Lu.K, Lu.N, Lu.r
+        mk = lambda L, pack: dict(il=dev(L.inv_lambda), L2=dev(L.L2), bias=dev(L.bias), wp=pack(dev(L.qw), dev(L.sw)))
+        pack = svdq.pack_weight_mxfp4 if fmt == "mxfp4" else svdq.pack_weight_e3m2
+        U, Dn = mk(Lu, pack), mk(Ld, pack)
+        U["l1p"] = svdq.pack_lowrank_down(dev(Lu.L1), U["il"])
+        Dn["l1p"] = svdq.pack_lowrank_down(dev(Ld.L1), Dn["il"])
+        x = dev(wu.x["x"])
+        y = torch.empty((M, F), dtype=torch.bfloat16, device="cuda")
+        yo = torch.empty((M, D), dtype=torch.bfloat16, device="cuda")
+        rho_u, rho_d = wu.tables["e0"][0], wd.tables["e0"][0]
+        if fmt == "mxfp4":
+            a = svdq.quantize_act_mxfp4(x, U["il"], rho_u, U["l1p"], r)
+            up = lambda: svdq.linear_mxfp4(a[0], a[1], U["wp"], F, a[2], U["L2"], U["bias"], out=y)
+            up()
+            q = svdq.quantize_act_gelu(svdq.FMT_MXFP4, y, Dn["il"], rho_d, Dn["l1p"], r)
+            qn = tuple(torch.empty_like(t) for t in q)
+            quant = lambda: svdq.quantize_act_gelu(svdq.FMT_MXFP4, y, Dn["il"], rho_d, Dn["l1p"], r, out=q)
+            down = lambda b: svdq.linear_mxfp4(b[0], b[1], Dn["wp"], D, b[2], Dn["L2"], Dn["bias"], out=yo)
+            upn = lambda: svdq.linear_mxfp4_next(a[0], a[1], U["wp"], F, Dn["il"], rho_d, a[2], U["L2"], U["bias"],
+                                                 gelu=True, next_l1_packed=Dn["l1p"], next_r=r, out=qn)
+            same = lambda: torch.equal(q[0], qn[0]) and torch.equal(q[1], qn[1])
+        else:
+            a = svdq.quantize_act_e3m2(x, U["il"], rho_u, U["l1p"], r, want_sx=False)
+            up = lambda: svdq.linear_w4a4_e3m2(a[0], U["wp"], F, a[2], U["L2"], U["bias"], out=y)
+            up()
+            q = svdq.quantize_act_gelu(svdq.FMT_INT4_E3M2, y, Dn["il"], rho_d, Dn["l1p"], r)
+            q = (q[0], None, q[2])
+            qn = (svdq.ActE3M2(torch.empty_like(q[0].buf), M, F), None, torch.empty_like(q[2]))
+            quant = lambda: svdq.quantize_act_gelu(svdq.FMT_INT4_E3M2, y, Dn["il"], rho_d, Dn["l1p"], r, out=q)
+            down = lambda b: svdq.linear_w4a4_e3m2(b[0], Dn["wp"], D, b[2], Dn["L2"], Dn["bias"], out=yo)
+            upn = lambda: svdq.linear_w4a4_e3m2_next(a[0], U["wp"], F, Dn["il"], rho_d, a[2], U["L2"], U["bias"],
+                                                     gelu=True, next_l1_packed=Dn["l1p"], next_r=r, out=qn)
+            same = lambda: torch.equal(q[0].buf, qn[0].buf)
+
+        def timed(fn, n=max(4, args.steps // 5)):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+
+        quant(), upn()
+        torch.cuda.synchronize()
+        rec = {"operands_identical": bool(same()),
+               "h_rel_diff": float((q[2] - qn[2]).norm() / q[2].norm()),
+               "up_ms": timed(up), "gelu_quantize_ms": timed(quant), "down_ms": timed(lambda: down(q)),
+               "up_emitting_ms": timed(upn),
+               "unfused_chain_ms": timed(lambda: (up(), quant(), down(q))),
+               "fused_chain_ms": timed(lambda: (upn(), down(qn)))}
+        rec["fused_over_unfused"] = rec["fused_chain_ms"] / rec["unfused_chain_ms"]
+        return rec
+
     METRIC = "W4A4 SVDQuant linear effective TOPS + % int8-MFMA peak; quantize pass GB/s"
     DTYPE = ("int4 x int4 -> exact integer group sums (codes held as E3M2 fields, FP6 MFMA, binary32 accumulate), "
              "fp32 dequant, bf16 out")
@@ -304,6 +369,12 @@ def main():
         out["mxfp4_variant"] = variant(measure("mxfp4"), "mxfp4", MXFP4, w.name)
     if args.cpu_rows > 0:
         out["cpu_baseline"] = cpu_baseline(w, L, args.cpu_rows)
+    if args.ffn_chain:
+        del w, L
+        out["ffn_chain"] = {"workload": "c3_ffn_up -> GELU -> c4_ffn_down: M=32760, 5120 -> 13824 -> 5120, r=32",
+                            "int4_e3m2": ffn_chain("e3m2")}
+        if not args.skip_mxfp4:
+            out["ffn_chain"]["mxfp4"] = ffn_chain("mxfp4")
     print(json.dumps(out))
 
 
