@@ -401,9 +401,13 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
         else if (k == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
         else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * NDMA) : "memory");
     };
+    const int64_t mw = m0 + wm * (32 * MT);                   // first token of this wave's tile
     {
+        // the first stages are requested; while they are in flight y starts as the low-rank term plus the bias
+        // (eq. 7, 11), so that the latency of those loads hides here instead of standing at the end of the tile
         const int pre = nstages < NS ? nstages : NS;
         for (int s = 0; s < pre; ++s) stage_issue(s);
+        add_lowrank_bias<2, MT>(y, h, L2, bias, mw, n0 + wn * 64, M, N, r, lane);
         wait_stages(pre - 1);
     }
     __syncthreads();
@@ -480,9 +484,7 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may still be writing this block's LDS when it ends
 
-    // ---- epilogue (c): low-rank up-projection on the bf16 matrix cores, bias, store
-    const int64_t mw = m0 + wm * (32 * MT);                   // first token of this wave's tile
-    add_lowrank_bias<2, MT>(y, h, L2, bias, mw, n0 + wn * 64, M, N, r, lane);
+    // ---- epilogue (c): store (the low-rank term and the bias are already in y)
     if constexpr (MODE != MX_LAYER) {
         const int gq = (n0 + wn * 64) >> 6;                    // this wave's 64-group of the next layer (stage nt, slot wn)
         const float* il = nx.inv_lambda + n0 + wn * 64 + kh * 32;
