@@ -170,3 +170,69 @@ def test_block_720p_schedule(svdq, oracle, block720p, expert):
             check_layer(svdq, oracle, f"{w.name}/{expert}/step{step}/{lin}", xb, xd, DL.L, DL, rho,
                         n_sample=256, whole=int(si == 0 and lin in ("q", "ffn_down")), seed=step)
             del xd
+
+
+@pytest.mark.parametrize("fmt", ["int4", "mxfp4"])
+def test_ffn_chain_emitting_epilogue_fullsize(svdq, oracle, fmt):
+    """Up-projection (C3) -> GELU -> quantise for the down-projection (C4) at M = 32760, with the GEMM epilogue that
+    emits the operands: whole buffers byte-identical to the un-fused sequence; on a row sample (rows are independent
+    along the whole chain) bit-exact against the oracle's chain wherever the two sides' bf16 activations agree."""
+    from tests.helpers import unpack_act_e3m2_np
+    wu, wd = synth.workload(2, fmt=fmt), synth.workload(3, fmt=fmt)
+    Lu, Ld = wu.layers["e0/lin"], wd.layers["e0/lin"]
+    M, F, r = wu.M, Lu.N, Lu.r
+    progress(f"ffn chain {fmt}: inputs generated (M={M})")
+    x = wu.x["x"]
+    ilu, ild = dev(Lu.inv_lambda), dev(Ld.inv_lambda)
+    l1u, l1d = svdq.pack_lowrank_down(dev(Lu.L1), ilu), svdq.pack_lowrank_down(dev(Ld.L1), ild)
+    L2u, bu = dev(Lu.L2), dev(Lu.bias)
+    rho_u, rho_d = wu.tables["e0"][0], wd.tables["e0"][0]
+    S = synth.sample_rows(M, 256, 5)
+    St = torch.from_numpy(S).cuda()
+    xs = np.ascontiguousarray(x[S])
+    if fmt == "mxfp4":
+        wp = svdq.pack_weight_mxfp4(dev(Lu.qw), dev(Lu.sw))
+        a = svdq.quantize_act_mxfp4(dev(x), ilu, rho_u, l1u, r)
+        y = svdq.linear_mxfp4(a[0], a[1], wp, F, a[2], L2u, bu)
+        ref = svdq.quantize_act_gelu(svdq.FMT_MXFP4, y, ild, rho_d, l1d, r)
+        got = svdq.linear_mxfp4_next(a[0], a[1], wp, F, ild, rho_d, a[2], L2u, bu, gelu=True, next_l1_packed=l1d, next_r=r)
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1])
+        oq, os_ = oracle.quantize_act_mxfp4(xs, Lu.inv_lambda, rho_u)
+        orc = oracle.linear_mxfp4(oq, os_, Lu.qw, Lu.sw, oracle.lowrank_down(xs, Lu.inv_lambda, Lu.L1), Lu.L2, Lu.bias,
+                                  want=("ybf16",))
+        xg = oracle.gelu_tanh_bf16(orc["ybf16"])
+        oq2, os2 = oracle.quantize_act_mxfp4(xg, Ld.inv_lambda, rho_d)
+        gq, gs = svdq.mx_to_token_major(got[0][:, St].contiguous(), got[1][:, St].contiguous(), F)
+        gq, gs, blk = gq.cpu().numpy(), gs.cpu().numpy(), 32
+        codes_g, codes_o = gq.reshape(len(S), -1, blk // 2), oq2.reshape(len(S), -1, blk // 2)
+    else:
+        wp = svdq.pack_weight_e3m2(dev(Lu.qw), dev(Lu.sw))
+        a = svdq.quantize_act_e3m2(dev(x), ilu, rho_u, l1u, r, want_sx=False)
+        y = svdq.linear_w4a4_e3m2(a[0], wp, F, a[2], L2u, bu)
+        ref = svdq.quantize_act_gelu(svdq.FMT_INT4_E3M2, y, ild, rho_d, l1d, r)
+        got = svdq.linear_w4a4_e3m2_next(a[0], wp, F, ild, rho_d, a[2], L2u, bu, gelu=True, next_l1_packed=l1d, next_r=r)
+        torch.cuda.synchronize()
+        # rows M..Mp-1 of the operand buffer are padding that neither call writes; M is a multiple of 4 here
+        assert M % 4 == 0 and torch.equal(got[0].buf, ref[0].buf) and torch.equal(got[1], ref[1])
+        oq, os_ = oracle.quantize_act(xs, Lu.inv_lambda, rho_u)
+        orc = oracle.linear(oq, os_, Lu.qw, Lu.sw, oracle.lowrank_down(xs, Lu.inv_lambda, Lu.L1), Lu.L2, Lu.bias,
+                            want=("ybf16",))
+        xg = oracle.gelu_tanh_bf16(orc["ybf16"])
+        oq2, os2 = oracle.quantize_act(xg, Ld.inv_lambda, rho_d)
+        gs = got[1][:, St].t().contiguous().cpu().numpy()
+        qn = svdq.unpack_act_e3m2(got[0])                                       # [F/64, M, 32] nibbles
+        gq, blk = qn[:, St].permute(1, 0, 2).reshape(len(S), -1).cpu().numpy(), 64
+        codes_g, codes_o = gq.reshape(len(S), -1, blk // 2), oq2.reshape(len(S), -1, blk // 2)
+    hrel = float((got[2].double() - ref[2].double()).norm() / ref[2].double().norm())
+    assert hrel <= 2e-6, hrel
+    progress(f"ffn chain {fmt}: operands byte-identical to the un-fused sequence on the whole buffers, h' rel diff {hrel:.2e}")
+    same = (host_bits(y[St]) == orc["ybf16"]).reshape(len(S), F // blk, blk).all(axis=2)
+    assert same.mean() > 0.03, same.mean()
+    sg, so = (gs, os2) if fmt == "mxfp4" else (gs.view(np.uint32), os2.view(np.uint32))
+    assert np.array_equal(sg[same], so[same]) and np.array_equal(codes_g[same], codes_o[same])
+    oh2 = oracle.lowrank_down(xg, Ld.inv_lambda, Ld.L1)
+    hd = rel_fro(got[2][St].cpu().numpy(), oh2)
+    assert hd <= 3e-3, hd
+    progress(f"ffn chain {fmt}: oracle chain bit-exact on {same.mean() * 100:.1f} % of the sampled (token, block) pairs "
+             f"(those whose activations agree), h' rel {hd:.1e}")
