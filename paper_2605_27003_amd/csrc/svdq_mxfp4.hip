@@ -588,6 +588,228 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     }
 }
 
+
+// The eight-wave kernel as ONE block per CU that walks its tiles.  A block that is alone on its CU shows every
+// tile's start and end: filling the ring (12 k clocks when all CUs of a round of blocks ask at once) and the
+// store (6 k) stand beside a K loop of 62 k.  Here the ring never drains between tiles: the slots that the last
+// stages of a tile hand over take the first stages of the block's NEXT tile, so those arrive during the end of the
+// loop and the store, and the store transposes through its own LDS area behind a three-slot ring.  Tiles are taken
+// in the same XCD-aware order (tile ids b, b + gridDim, ...; gridDim a multiple of 8 keeps a block on one XCD's
+// share).  Same arithmetic, same order of operations per output as gemm_mx_kernel.
+template <int MT>
+__global__ __launch_bounds__(512, 1)
+void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__ sxe,
+                               const uint4* __restrict__ wfrag, const uint16_t* __restrict__ wscale,
+                               const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
+                               int64_t M, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
+                               int mtiles, int ntiles) {
+    constexpr int WNC = 4;
+    using G = MxGeom<MT, WNC>;
+    constexpr int BM = G::BM, NDMA = G::NDMA, NS = 3;
+    constexpr uint32_t STORE_ROWS = 32;                               // the store goes through LDS 32 tokens at a time
+    __shared__ __attribute__((aligned(16))) uint8_t ring[NS * G::STAGE + 2 * WNC * STORE_ROWS * YROW];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const int l32 = lane & 31, kh = lane >> 5;
+    const int ng = K >> 6;
+    const int nstages = (ng + 1) >> 1;                                // >= NS + 1 (the launcher sees to it)
+    const uint32_t ring0 = (uint32_t)(uintptr_t)(lds_byte*)ring;
+    const uint32_t store0 = ring0 + NS * G::STAGE + wave * STORE_ROWS * YROW;
+
+    // tile ids: the one-tile kernel's decode of blockIdx.x
+    const int total = ((mtiles + 63) / 64) * 64 * ntiles;
+    auto decode = [&](const int id, int& mt, int& nt) {
+        const int xcd = id & 7, idx = id >> 3;
+        const int sm = idx / (8 * ntiles), rem = idx - sm * (8 * ntiles);
+        nt = rem >> 3;
+        mt = (sm * 8 + (rem & 7)) * 8 + xcd;
+    };
+    auto next_valid = [&](int id) {
+        for (id += gridDim.x; id < total; id += gridDim.x) {
+            int mt, nt;
+            decode(id, mt, nt);
+            if (mt < mtiles) return id;
+        }
+        return -1;
+    };
+
+    // ---- staging (the eight-wave assignment of gemm_mx_kernel); what depends on the tile sits in TileAddr
+    const int cj = wave >> 2, sp = (wave >> 1) & 1, q0 = 2 * (wave & 1), nb0 = 2 * (wave & 3);
+    const int sxw = wave & 3, swp = wave & 3;
+    const uint32_t vl16 = lane * 16;
+    const uint32_t vw[2] = {(uint32_t)((nb0 + 0) * ng * 1024) + vl16, (uint32_t)((nb0 + 1) * ng * 1024) + vl16};
+    const uint32_t vsw = (uint32_t)(kh * nstages * 128 + l32 * 4);
+    const size_t sc_stride = (wave < 4) ? (size_t)M * 4 : (size_t)128;
+    const uint32_t sc_lds = (wave < 4) ? G::OFF_SX + sxw * 256 : G::OFF_SW + swp * 256;
+    struct TileAddr {
+        uint32_t va[2], vsc;
+        const uint8_t* sc_base;
+        int64_t m0;
+        int n0, nbB;
+    };
+    auto tile_addr = [&](const int id) {
+        int mt, nt;
+        decode(id, mt, nt);
+        TileAddr t;
+        t.m0 = (int64_t)mt * BM;
+        t.n0 = nt * G::BN;
+        t.nbB = t.n0 >> 5;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int64_t row = t.m0 + (q0 + q) * 64 + lane;
+            t.va[q] = (uint32_t)(((row < M) ? row : (M - 1)) * 32 + sp * 16);
+        }
+        const int64_t srow = t.m0 + sxw * 64 + lane;
+        t.vsc = (wave < 4) ? (uint32_t)(((srow < M) ? srow : (M - 1)) * 4) : vsw;
+        t.sc_base = (wave < 4) ? reinterpret_cast<const uint8_t*>(sxe)
+                               : reinterpret_cast<const uint8_t*>(wscale + (size_t)(t.nbB + 2 * swp) * nstages * 64);
+        return t;
+    };
+    auto stage_issue = [&](const TileAddr& t, const int s, const uint32_t slot) {
+        const int g = (2 * s + cj < ng) ? 2 * s + cj : ng - 1;        // odd tail: re-read (its scale bytes are zero)
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+            dma16(qx + (size_t)g * M * 32, t.va[q], slot + G::OFF_A + ((cj * 2 + sp) * BM + (q0 + q) * 64) * 16);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            dma16(wfrag + ((size_t)t.nbB * ng + g) * 64, vw[i], slot + G::OFF_W + (cj * 2 * WNC + nb0 + i) * 1024);
+        dma4(t.sc_base + (size_t)s * sc_stride, t.vsc, slot + sc_lds);
+    };
+
+    const uint32_t rd_a = G::OFF_A + (kh * BM + wm * (32 * MT) + l32) * 16;
+    const uint32_t rd_w = G::OFF_W + (wn * 2 * 64 + lane) * 16;
+    const uint32_t rd_sx = G::OFF_SX + ((wm * (32 * MT) + l32) * 2 + kh) * 2;
+    const uint32_t rd_sw = G::OFF_SW + (wn * 2 * 64 + lane) * 2;
+
+    struct Operands {
+        uint4 wf[2], xf[MT];
+        uint32_t sw[2], sx[MT];
+    };
+    Operands op0, op1;
+    auto fetch = [&](Operands& o, const uint32_t slot, const int j) {
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            o.wf[ni] = lds_read16_pinned(slot + rd_w + j * 2048 * WNC + ni * 1024);
+            o.sw[ni] = lds_read2_pinned(slot + rd_sw + ni * 128);
+        }
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi) {
+            o.xf[mi] = lds_read16_pinned(slot + rd_a + j * 32 * BM + mi * 512);
+            o.sx[mi] = lds_read2_pinned(slot + rd_sx + mi * 128);
+        }
+    };
+    float16v y[2][MT];
+    auto mma_group = [&](const Operands& o, auto JC) {
+        constexpr int j = decltype(JC)::value;
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const int8v a = {(int)o.wf[ni].x, (int)o.wf[ni].y, (int)o.wf[ni].z, (int)o.wf[ni].w, 0, 0, 0, 0};
+#pragma unroll
+            for (int mi = 0; mi < MT; ++mi) {
+                const int8v b = {(int)o.xf[mi].x, (int)o.xf[mi].y, (int)o.xf[mi].z, (int)o.xf[mi].w, 0, 0, 0, 0};
+                y[ni][mi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, y[ni][mi], 4, 4, j, (int)o.sw[ni], j, (int)o.sx[mi]);
+            }
+        }
+    };
+    auto next_slot = [&](const uint32_t c) { return (c == ring0 + (NS - 1) * G::STAGE) ? ring0 : c + G::STAGE; };
+
+    int id = blockIdx.x;
+    {
+        int mt, nt;
+        decode(id, mt, nt);
+        if (mt >= mtiles) id = next_valid(id);
+    }
+    if (id < 0) return;
+    TileAddr T = tile_addr(id);
+    uint32_t cur = ring0;                                             // slot of the current tile's stage 0
+    {
+        uint32_t sl = cur;
+        for (int s = 0; s < NS; ++s) {
+            stage_issue(T, s, sl);
+            sl = next_slot(sl);
+        }
+    }
+
+    // What a stage does once its first group is multiplied: the stage after it (of this tile or of the next) is awaited
+    // and made visible, and the slot takes stage s + NS of this tile (SAME) or, when the tile has no such stage left,
+    // stage s + NS - nstages of the block's next tile (NEXT).  END: the tile's last stage, whose successor's operands
+    // the next tile requests itself.  The block's last tile "prefetches" its own first stages again: three stages
+    // nobody reads, for a loop without a third variant.
+    while (true) {
+        const int nid = next_valid(id);
+        const TileAddr T1 = tile_addr(nid >= 0 ? nid : id);
+        const int64_t mw = T.m0 + wm * (32 * MT);
+        // the per-lane address arithmetic of the low-rank term and of the store is the same for every tile; hidden
+        // from the compiler here, it is redone per tile instead of being kept in (spilled) registers across the K loops
+        int lane_t = lane;
+        asm volatile("" : "+v"(lane_t));
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < MT; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) y[a][b][i] = 0.0f;
+        // y starts as the low-rank term plus the bias (eq. 7, 11); its loads return behind the transfers already
+        // requested for this tile, which were requested a stage or more ago
+        add_lowrank_bias<2, MT>(y, h, L2, bias, mw, T.n0 + wn * 64, M, N, r, lane_t);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * NDMA) : "memory");    // stage 0 of this tile
+        __syncthreads();
+        fetch(op0, cur, 0);
+
+        auto stage_body = [&](const int s, const uint32_t c, const uint32_t nxt, auto SAMEC, auto ENDC) {
+            constexpr bool SAME = decltype(SAMEC)::value, END = decltype(ENDC)::value;
+            fetch(op1, c, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_group(op0, IC<0>{});
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NDMA) : "memory");
+            __syncthreads();
+            if (SAME) stage_issue(T, s + NS, c);
+            else stage_issue(T1, s + NS - nstages, c);
+            if (!END) fetch(op0, nxt, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_group(op1, IC<1>{});
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        int s = 0;
+        for (; s + NS < nstages; ++s) {
+            const uint32_t nxt = next_slot(cur);
+            stage_body(s, cur, nxt, IC<1>{}, IC<0>{});
+            cur = nxt;
+        }
+        for (; s + 1 < nstages; ++s) {
+            const uint32_t nxt = next_slot(cur);
+            stage_body(s, cur, nxt, IC<0>{}, IC<0>{});
+            cur = nxt;
+        }
+        stage_body(s, cur, next_slot(cur), IC<0>{}, IC<1>{});
+        cur = next_slot(cur);                                         // where the next tile's stage 0 went
+
+        // ---- store: the ring belongs to the next tile by now, so the transposition uses the area behind it
+        if (out_f32) {
+            store_tile_f32<2, MT>(y, reinterpret_cast<float*>(yout), ldy, mw, T.n0 + wn * 64, M, lane_t);
+        } else {
+            uint16_t* yw = reinterpret_cast<uint16_t*>(yout) + mw * ldy + T.n0 + wn * 64;
+            auto store_chunk = [&](auto CC) {                          // 32 tokens: accumulator block c of both n-blocks
+                constexpr int c = decltype(CC)::value;
+                store_tile_bf16<1>([&](int ni, int mi, int i) { return y[ni][c + mi][i]; },
+                                   store0, lane_t, yw + (int64_t)(32 * c) * ldy, ldy, M - mw - 32 * c);
+            };
+            static_assert(MT == 4, "four 32-token chunks");
+            store_chunk(IC<0>{});
+            store_chunk(IC<1>{});
+            store_chunk(IC<2>{});
+            store_chunk(IC<3>{});
+        }
+        if (nid < 0) break;
+        id = nid;
+        T = T1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may still be writing this block's LDS when it ends
+}
+
 }  // namespace
 
 size_t packed_weight_mx_bytes(int N, int K) { return mx_wfrag_bytes(N, K) + mx_wscale_bytes(N, K); }
@@ -629,7 +851,13 @@ hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w
     const uint16_t* wsc = (const uint16_t*)(base + mx_wfrag_bytes(N, K));
     const int mtiles = (int)((M + 64 * MT - 1) / (64 * MT));
     const int sms = (mtiles + 63) / 64;
-    if (N % 256 == 0) {                      // 256 x 256 block tiles, eight waves, one block per CU
+    if (N % 256 == 0 && K >= 512 && (int64_t)mtiles * (N / 256) >= 2 * 256) {
+        // 256 x 256 block tiles, eight waves, one block per CU walking its tiles (256 CUs)
+        const int ntiles = N / 256;
+        hipLaunchKernelGGL((gemm_mx_persistent_kernel<MT>), dim3(256), dim3(512), 0, stream,
+                           qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
+                           M, N, K, r, y, ldy, out_f32, mtiles, ntiles);
+    } else if (N % 256 == 0) {               // 256 x 256 block tiles, eight waves, one block per CU and tile
         const int ntiles = N / 256;
         hipLaunchKernelGGL((gemm_mx_kernel<MT, 4, MX_LAYER>), dim3((unsigned)(sms * 64 * ntiles)), dim3(512), 0, stream,
                            qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
