@@ -277,13 +277,7 @@ struct MxGeom {
     static_assert(WNC == 2 || (WNC == 4 && MT == 4), "staging is written for 4 waves, or 8 waves with 256 tokens");
 };
 
-// MODE: MX_LAYER stores y.  MX_NEXT / MX_NEXT_GELU (four-wave geometry only): y never reaches HBM; the wave rounds
-// its tile to bf16, optionally applies GELU and runs the NEXT layer's kernel (a') on it.  A wave's 64 channels are two
-// MX blocks of the next layer's K axis: after lanes l and l + 32 have traded n-blocks a lane holds one whole block
-// of its token, so the shared exponent and the codes need no further exchange; the wave's share of
-// h' = x^' L1' is added to the zeroed h' with atomic adds (after the two waves that share tokens have been summed
-// in LDS).
-enum { MX_LAYER = 0, MX_NEXT = 1, MX_NEXT_GELU = 2 };
+// The next layer's side of the emitting epilogues.
 struct MxNext {
     const float* inv_lambda;     // [N]
     const uint4* l1p;            // packed L1' (K' = N) or null
@@ -293,6 +287,119 @@ struct MxNext {
     float rho;
     int r;
 };
+
+// Kernel (a') of the NEXT layer on a wave's finished tile (64 channels nw .. nw + 63 of tokens mw .. mw + 32 MT - 1):
+// round to bf16 (what the layer would have stored), optionally GELU, trade n-blocks between lanes l and l + 32 so
+// that a lane holds one whole MX block of its token, quantise it with the quantise kernel's own function, write
+// codes and scale byte.  If the next layer has a low-rank branch, hp[mi] returns the wave's share of h' for its
+// tokens ([token][j] in the accumulator layout: lane holds column j = lane % 32).
+template <int MT, bool GELU>
+__device__ __forceinline__ void emit_next_mx(const float16v (&y)[2][MT], const MxNext& nx, int64_t M, int64_t mw, int nw,
+                                             int lane, float16v (&hp)[MT]) {
+    const int l32 = lane & 31, kh = lane >> 5;
+    const int gq = nw >> 6;                                    // this wave's 64-group of the next layer
+    const float* il = nx.inv_lambda + nw + kh * 32;
+    uint4 bfrag[4][2];
+    if (nx.r > 0) {
+        const uint4* pb = nx.l1p + (size_t)gq * (4 * 2 * 64) + lane;
+#pragma unroll
+        for (int sI = 0; sI < 4; ++sI) {
+            bfrag[sI][0] = pb[(sI * 2 + 0) * 64];
+            bfrag[sI][1] = pb[(sI * 2 + 1) * 64];
+        }
+    }
+#pragma unroll
+    for (int mi = 0; mi < MT; ++mi) {
+        // register 4 q + j of y[ni][mi] is channel 32 ni + 8 q + 4 kh + j of token mw + 32 mi + l32
+        uint32_t pk[2][8];
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+                uint32_t w = f2_bf16_rne(y[ni][mi][2 * d], y[ni][mi][2 * d + 1]);
+                if (GELU) w = gelu_tanh_bf16x2(w);
+                pk[ni][d] = w;
+            }
+        uint4 xc[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            // first result: own value in lanes 0..31, the lower lanes' second operand in lanes 32..63;
+            // second result: the upper lanes' first operand in lanes 0..31, own value in lanes 32..63
+            const auto e0 = __builtin_amdgcn_permlane32_swap(pk[0][2 * q], pk[1][2 * q], false, false);
+            const auto e1 = __builtin_amdgcn_permlane32_swap(pk[0][2 * q + 1], pk[1][2 * q + 1], false, false);
+            xc[q] = uint4{e0[0], e1[0], e0[1], e1[1]};         // channels 32 kh + 8 q + 0..7: MX block 2 gq + kh
+        }
+        uint4 codes;
+        uint32_t e8;
+        quantize_block_mx(xc, il, nx.rho, codes, e8);
+        const int64_t row = mw + mi * 32 + l32;
+        if (row < M) {
+            *reinterpret_cast<uint4*>(nx.qx + ((size_t)gq * M + row) * 32 + kh * 16) = codes;
+            nx.sxe[(((size_t)(gq >> 1) * M + row) * 2 + kh) * 2 + (gq & 1)] = (uint8_t)e8;
+        }
+        if (nx.r > 0) {
+            float16v acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+#pragma unroll
+            for (int sI = 0; sI < 4; ++sI) {
+                const bf16x8 av = __builtin_bit_cast(bf16x8, xc[sI]);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sI][0]), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sI][1]), acc, 0, 0, 0);
+            }
+            hp[mi] = acc;
+        }
+    }
+}
+
+// The WNC waves of a block that share tokens (wn = 0 .. WNC - 1, same wm) sum their shares of h' through LDS, one
+// after the other into the same area (`part`: this wm's [MT * 16][64] floats, block-uniform control flow), and wave
+// wn = 0 adds the block's sum to the zeroed h' with atomic adds.  Register (mi, i) of lane (l32, kh) is token
+// mw + 4 kh + [32 mi + 8 (i / 4) + i % 4], column l32.
+template <int MT, int WNC>
+__device__ __forceinline__ void add_next_h(float16v (&hp)[MT], float* part, int wn, const MxNext& nx, int64_t M, int64_t mw,
+                                           int lane) {
+    const int l32 = lane & 31, kh = lane >> 5;
+    part += lane;
+#pragma unroll
+    for (int w = WNC - 1; w >= 1; --w) {
+        if (wn == w) {
+#pragma unroll
+            for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float v = hp[mi][i];
+                    if (w != WNC - 1) v += part[(mi * 16 + i) * 64];
+                    part[(mi * 16 + i) * 64] = v;
+                }
+        }
+        __syncthreads();
+    }
+    if (wn == 0) {
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) hp[mi][i] += part[(mi * 16 + i) * 64];
+        const int64_t first = mw + 4 * kh;
+        const int left = (l32 < nx.r && first < M) ? (int)((M - first < 32 * MT) ? M - first : 32 * MT) : 0;
+        float* hb = nx.h + first * nx.r + l32;
+#pragma unroll
+        for (int mi = 0; mi < MT; ++mi)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int rl = 32 * mi + 8 * (i >> 2) + (i & 3);
+                if (rl < left) unsafeAtomicAdd(hb + rl * nx.r, hp[mi][i]);
+            }
+    }
+}
+
+// MODE: MX_LAYER stores y.  MX_NEXT / MX_NEXT_GELU (four-wave geometry only): y never reaches HBM; the wave rounds
+// its tile to bf16, optionally applies GELU and runs the NEXT layer's kernel (a') on it.  A wave's 64 channels are two
+// MX blocks of the next layer's K axis: after lanes l and l + 32 have traded n-blocks a lane holds one whole block
+// of its token, so the shared exponent and the codes need no further exchange; the wave's share of
+// h' = x^' L1' is added to the zeroed h' with atomic adds (after the two waves that share tokens have been summed
+// in LDS).
+enum { MX_LAYER = 0, MX_NEXT = 1, MX_NEXT_GELU = 2 };
 
 template <int MT, int WNC, int MODE>
 __global__ __launch_bounds__(128 * WNC, (WNC == 2) ? 2 : 1)
@@ -486,87 +593,11 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
 
     // ---- epilogue (c): store (the low-rank term and the bias are already in y)
     if constexpr (MODE != MX_LAYER) {
-        const int gq = (n0 + wn * 64) >> 6;                    // this wave's 64-group of the next layer (stage nt, slot wn)
-        const float* il = nx.inv_lambda + n0 + wn * 64 + kh * 32;
-        uint4 bfrag[4][2];
-        if (nx.r > 0) {
-            const uint4* pb = nx.l1p + (size_t)gq * (4 * 2 * 64) + lane;
-#pragma unroll
-            for (int sI = 0; sI < 4; ++sI) {
-                bfrag[sI][0] = pb[(sI * 2 + 0) * 64];
-                bfrag[sI][1] = pb[(sI * 2 + 1) * 64];
-            }
-        }
         float16v hp[MT];
-#pragma unroll
-        for (int mi = 0; mi < MT; ++mi) {
-            // register 4 q + j of y[ni][mi] is channel 32 ni + 8 q + 4 kh + j of token mw + 32 mi + l32
-            uint32_t pk[2][8];
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-                for (int d = 0; d < 8; ++d) {
-                    uint32_t w = f2_bf16_rne(y[ni][mi][2 * d], y[ni][mi][2 * d + 1]);
-                    if (MODE == MX_NEXT_GELU) w = gelu_tanh_bf16x2(w);
-                    pk[ni][d] = w;
-                }
-            uint4 xc[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                // first result: own value in lanes 0..31, the lower lanes' second operand in lanes 32..63;
-                // second result: the upper lanes' first operand in lanes 0..31, own value in lanes 32..63
-                const auto e0 = __builtin_amdgcn_permlane32_swap(pk[0][2 * q], pk[1][2 * q], false, false);
-                const auto e1 = __builtin_amdgcn_permlane32_swap(pk[0][2 * q + 1], pk[1][2 * q + 1], false, false);
-                xc[q] = uint4{e0[0], e1[0], e0[1], e1[1]};     // channels 32 kh + 8 q + 0..7: MX block 2 gq + kh
-            }
-            uint4 codes;
-            uint32_t e8;
-            quantize_block_mx(xc, il, nx.rho, codes, e8);
-            const int64_t row = mw + mi * 32 + l32;
-            if (row < M) {
-                *reinterpret_cast<uint4*>(nx.qx + ((size_t)gq * M + row) * 32 + kh * 16) = codes;
-                nx.sxe[(((size_t)(gq >> 1) * M + row) * 2 + kh) * 2 + (gq & 1)] = (uint8_t)e8;
-            }
-            if (nx.r > 0) {
-                float16v acc;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
-#pragma unroll
-                for (int sI = 0; sI < 4; ++sI) {
-                    const bf16x8 av = __builtin_bit_cast(bf16x8, xc[sI]);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sI][0]), acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, bfrag[sI][1]), acc, 0, 0, 0);
-                }
-                hp[mi] = acc;                                  // [token][j]: lane holds column j = l32
-            }
-        }
+        emit_next_mx<MT, MODE == MX_NEXT_GELU>(y, nx, M, mw, n0 + wn * 64, lane, hp);
         if (nx.r > 0) {
             __syncthreads();                                   // every wave is done with the operand ring
-            float* part = reinterpret_cast<float*>(ring) + wm * (MT * 16 * 64) + lane;
-            if (wn == 1) {
-#pragma unroll
-                for (int mi = 0; mi < MT; ++mi)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) part[(mi * 16 + i) * 64] = hp[mi][i];
-            }
-            __syncthreads();
-            if (wn == 0) {
-#pragma unroll
-                for (int mi = 0; mi < MT; ++mi)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) hp[mi][i] += part[(mi * 16 + i) * 64];
-                // register (mi, i) is token mw + 4 kh + [32 mi + 8 (i / 4) + i % 4] of column l32
-                const int64_t first = mw + 4 * kh;
-                const int left = (l32 < nx.r && first < M) ? (int)((M - first < 32 * MT) ? M - first : 32 * MT) : 0;
-                float* hb = nx.h + first * nx.r + l32;
-#pragma unroll
-                for (int mi = 0; mi < MT; ++mi)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int rl = 32 * mi + 8 * (i >> 2) + (i & 3);
-                        if (rl < left) unsafeAtomicAdd(hb + rl * nx.r, hp[mi][i]);
-                    }
-            }
+            add_next_h<MT, WNC>(hp, reinterpret_cast<float*>(ring) + wm * (MT * 16 * 64), wn, nx, M, mw, lane);
         }
         return;
     }
@@ -787,7 +818,9 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
         stage_body(s, cur, next_slot(cur), IC<0>{}, IC<1>{});
         cur = next_slot(cur);                                         // where the next tile's stage 0 went
 
-        // ---- store: the ring belongs to the next tile by now, so the transposition uses the area behind it
+        // ---- store: the ring belongs to the next tile by now, so the transposition uses the area behind it.  (The
+        // emitting epilogues stay with the four-wave kernel: alone on its CU a block would run their vector-ALU work,
+        // about 10 k clocks per tile, beside nothing; measured 1.83 ms against 1.58 ms for the C3 up-projection.)
         if (out_f32) {
             store_tile_f32<2, MT>(y, reinterpret_cast<float*>(yout), ldy, mw, T.n0 + wn * 64, M, lane_t);
         } else {
@@ -842,6 +875,12 @@ hipError_t launch_quantize_mx(const void* x, int64_t ldx, const float* inv_lambd
                 : launch_quantize_mx_any<false>(x, ldx, inv_lambda, rho, l1p, M, K, r, qx, sxe, h, stream);
 }
 
+// the tile-walking kernel needs full 256-channel tiles, a K loop longer than its ring, and pays once every CU has
+// at least two tiles
+static inline bool walks_tiles(int mtiles, int N, int K) {
+    return N % 256 == 0 && K >= 512 && (int64_t)mtiles * (N / 256) >= 2 * 256;
+}
+
 hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w_packed,
                             const float* h, const void* L2, const float* bias,
                             int64_t M, int N, int K, int r, void* y, int64_t ldy, int out_f32,
@@ -851,8 +890,7 @@ hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w
     const uint16_t* wsc = (const uint16_t*)(base + mx_wfrag_bytes(N, K));
     const int mtiles = (int)((M + 64 * MT - 1) / (64 * MT));
     const int sms = (mtiles + 63) / 64;
-    if (N % 256 == 0 && K >= 512 && (int64_t)mtiles * (N / 256) >= 2 * 256) {
-        // 256 x 256 block tiles, eight waves, one block per CU walking its tiles (256 CUs)
+    if (walks_tiles(mtiles, N, K)) {         // 256 x 256 block tiles, eight waves, one block per CU walking its tiles
         const int ntiles = N / 256;
         hipLaunchKernelGGL((gemm_mx_persistent_kernel<MT>), dim3(256), dim3(512), 0, stream,
                            qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
