@@ -467,17 +467,18 @@ def debug_scale_chain(a, rho):
 class W4A4Linear:
     """One quantised linear resident in HBM: packed weights and low-rank factors, reusable output buffers.
 
-    container "e3m2" (default) runs the FP6 matrix-core path, "nibble" the int8 one on 4-bit storage."""
+    container "e3m2" (default) runs the int4 layer on the FP6 matrix cores, "nibble" the same layer on 4-bit storage
+    and the int8 matrix cores, "mxfp4" the MXFP4 format (qw then holds E2M1 codes and sw [K/32, N] E8M0 bytes)."""
 
     def __init__(self, inv_lambda, L1_bf16, L2_bf16, qw, sw, bias, container="e3m2"):
-        assert container in ("e3m2", "nibble")
+        assert container in ("e3m2", "nibble", "mxfp4")
         self.container = container
         self.N, self.K = qw.shape[0], qw.shape[1] * 2
         self.r = 0 if L1_bf16 is None else L1_bf16.shape[1]
         self.inv_lambda = inv_lambda
         self.l1_packed = pack_lowrank_down(L1_bf16, inv_lambda) if self.r else None
         self.L2 = L2_bf16 if self.r else None
-        self.w_packed = pack_weight_e3m2(qw, sw) if container == "e3m2" else pack_weight(qw, sw)
+        self.w_packed = {"e3m2": pack_weight_e3m2, "nibble": pack_weight, "mxfp4": pack_weight_mxfp4}[container](qw, sw)
         self.bias = bias
         self._bufs = None
 
@@ -488,25 +489,32 @@ class W4A4Linear:
                 sx = None
             else:
                 qx = torch.empty((self.K // 64, M, 32), dtype=torch.uint8, device=device)
-                sx = torch.empty((self.K // 64, M), dtype=torch.float32, device=device)
+                sx = (torch.empty((self.K // 64, M), dtype=torch.float32, device=device) if self.container == "nibble"
+                      else torch.empty(((self.K // 64 + 1) // 2, M, 2, 2), dtype=torch.uint8, device=device))
             h = torch.empty((M, self.r), dtype=torch.float32, device=device) if self.r else None
             y = torch.empty((M, self.N), dtype=torch.bfloat16, device=device)
             self._bufs = (qx, sx, h, y)
         return self._bufs
 
-    def quantize(self, x_bf16, rho):
-        qx, sx, h, _ = self.buffers(x_bf16.shape[0], x_bf16.device)
-        if self.container == "e3m2":
-            return quantize_act_e3m2(x_bf16, self.inv_lambda, rho, self.l1_packed, self.r, out=(qx, sx, h))
-        return quantize_act(x_bf16, self.inv_lambda, rho, self.l1_packed, self.r, out=(qx, sx, h))
+    def quantize(self, x_bf16, rho, gelu=False):
+        """Kernel (a) into the layer's buffers; gelu=True applies the feed-forward block's activation on the fly."""
+        out = self.buffers(x_bf16.shape[0], x_bf16.device)[:3]
+        if gelu:
+            fmt = {"e3m2": FMT_INT4_E3M2, "nibble": FMT_INT4, "mxfp4": FMT_MXFP4}[self.container]
+            return quantize_act_gelu(fmt, x_bf16, self.inv_lambda, rho, self.l1_packed, self.r, out=out)
+        fn = {"e3m2": quantize_act_e3m2, "nibble": quantize_act, "mxfp4": quantize_act_mxfp4}[self.container]
+        return fn(x_bf16, self.inv_lambda, rho, self.l1_packed, self.r, out=out)
 
     def gemm(self, qx, sx, h):
         if self.container == "e3m2":
             y = self.buffers(qx.M, qx.buf.device)[3]
             return linear_w4a4_e3m2(qx, self.w_packed, self.N, h, self.L2, self.bias, out=y)
         y = self.buffers(qx.shape[1], qx.device)[3]
-        return linear_w4a4(qx, sx, self.w_packed, self.N, h, self.L2, self.bias, out=y)
+        fn = linear_w4a4 if self.container == "nibble" else linear_mxfp4
+        return fn(qx, sx, self.w_packed, self.N, h, self.L2, self.bias, out=y)
 
-    def forward(self, x_bf16, rho):
-        qx, sx, h = self.quantize(x_bf16, rho)
+    def forward(self, x_bf16, rho, gelu=False):
+        qx, sx, h = self.quantize(x_bf16, rho, gelu)
         return self.gemm(qx, sx, h)
+
+

@@ -162,3 +162,23 @@ def test_full_size_configs(svdq, oracle, idx):
     orc = oracle.linear_mxfp4(np.ascontiguousarray(fq[S]), np.ascontiguousarray(fs[S]), L.qw, L.sw, oh, L.L2, L.bias)
     stats = check_y(host_bits(y16[St]), y32[St].cpu().numpy(), orc, w.name)
     print(f"{w.name} mxfp4 rho={rho}: whole-buffer codes/scales ok, y ok on {len(S)} rows {stats}", flush=True)
+
+
+def test_resident_layer_object_mxfp4_and_gelu(svdq, oracle):
+    """W4A4Linear with the MXFP4 container, and its gelu option (the down-projection of the feed-forward block taking the
+    up-projection's pre-activation): outputs against the oracle's layer on the oracle's activated tensor."""
+    from tests.helpers import rel_fro
+    M, K, N, r = 150, 512, 256, 32
+    x, _ = synth.make_x(33, M, K, outlier_count=3, outlier_scale=8.0, sigma=1.5)
+    xg = oracle.gelu_tanh_bf16(x)
+    cm = np.maximum(np.abs(synth.bf16_bits_to_f32(xg)).max(axis=0), 1e-3).astype(np.float32)
+    L = synth.make_layer(33, K, N, r, cm, fmt="mxfp4")
+    lin = svdq.W4A4Linear(dev(L.inv_lambda), dev(L.L1), dev(L.L2), dev(L.qw), dev(L.sw), dev(L.bias), container="mxfp4")
+    oh = oracle.lowrank_down(xg, L.inv_lambda, L.L1)
+    oq, os_ = oracle.quantize_act_mxfp4(xg, L.inv_lambda, 0.9)
+    want = oracle.linear_mxfp4(oq, os_, L.qw, L.sw, oh, L.L2, L.bias)["y64"]
+    for y in (lin.forward(dev(x), 0.9, gelu=True), lin.forward(dev(xg), 0.9)):
+        torch.cuda.synchronize()
+        assert rel_fro(synth.bf16_bits_to_f32(host_bits(y)).astype(np.float64), want) <= 2e-3
+    ptr = y.data_ptr()
+    assert lin.forward(dev(xg), 0.9).data_ptr() == ptr               # buffers are reused for a repeated shape
