@@ -44,6 +44,7 @@
 #include "svdq_epilogue.h"
 #include "svdq_kernels.h"
 #include "svdq_lds.h"
+#include "svdq_tiles.h"
 
 namespace svdq {
 
@@ -85,17 +86,11 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
                  const uint4* __restrict__ wfrag, const uint2* __restrict__ sfrag, const uint4* __restrict__ cfrag,
                  const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
                  int64_t M, int64_t ldm, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
-                 int mtiles, int ntiles, int64_t dm0, int dmt, int32_t* __restrict__ dacc) {
+                 const TileGrid tg, int64_t dm0, int dmt, int32_t* __restrict__ dacc) {
     __shared__ __attribute__((aligned(16))) uint8_t ring[NSLOTS * STAGE_BYTES];   // slot of stage s: s % 3
 
-    // XCD-aware tile order: consecutive block ids go round-robin to the 8 XCDs,
-    // so give each XCD its own token tiles and walk them 8 at a time across n.
-    const int bid = blockIdx.x;
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int sm = idx / (8 * ntiles), rem = idx - sm * (8 * ntiles);
-    const int nt = rem >> 3;
-    const int mt = (sm * 8 + (rem & 7)) * 8 + xcd;
-    if (mt >= mtiles) return;
+    int mt, nt;                                 // XCD-aware tile order (svdq_tiles.h)
+    if (!tile_of(tg, blockIdx.x, mt, nt)) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);    // scalar: everything derived from it stays in SGPRs
@@ -456,10 +451,6 @@ hipError_t launch_pack_weight(const uint8_t* qw, const float* sw, int N, int K, 
     return hipGetLastError();
 }
 
-static inline unsigned grid_for(int mtiles, int ntiles) {
-    const int sms = (mtiles + 63) / 64;          // super-stripes of 8 XCDs x 8 token tiles
-    return (unsigned)(sms * 64 * ntiles);
-}
 
 hipError_t launch_linear(const uint8_t* qx, const float* sx, const void* w_packed,
                          const float* h, const void* L2, const float* bias,
@@ -470,9 +461,10 @@ hipError_t launch_linear(const uint8_t* qx, const float* sx, const void* w_packe
     const uint4* wf = (const uint4*)base;
     const uint2* sf = (const uint2*)(base + wfrag_bytes(N, K));
     const uint4* cf = (const uint4*)(base + wfrag_bytes(N, K) + sfrag_bytes(N, K));
-    hipLaunchKernelGGL(gemm_kernel<false>, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
+    const TileGrid tg = make_tile_grid(mtiles, ntiles);
+    hipLaunchKernelGGL(gemm_kernel<false>, dim3((unsigned)tile_ids(tg)), dim3(256), 0, stream,
                        qx, sx, wf, sf, cf, h, (const uint16_t*)L2, bias, M, M, N, K, r, y, ldy, out_f32,
-                       mtiles, ntiles, (int64_t)0, 0, (int32_t*)nullptr);
+                       tg, (int64_t)0, 0, (int32_t*)nullptr);
     return hipGetLastError();
 }
 
@@ -483,11 +475,12 @@ hipError_t launch_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, 
     const int mtiles = t1 - t0, ntiles = N / BN;
     const int64_t off = (int64_t)t0 * BM;
     // the integer accumulators need no scales: the DUMP instantiation never reads them
-    hipLaunchKernelGGL(gemm_kernel<true>, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
+    const TileGrid tg = make_tile_grid(mtiles, ntiles);
+    hipLaunchKernelGGL(gemm_kernel<true>, dim3((unsigned)tile_ids(tg)), dim3(256), 0, stream,
                        qx + off * 32, (const float*)nullptr, (const uint4*)w_packed, (const uint2*)nullptr,
                        (const uint4*)nullptr, (const float*)nullptr, (const uint16_t*)nullptr,
                        (const float*)nullptr, M - off, M, N, K, 0, (void*)nullptr, (int64_t)0, 0,
-                       mtiles, ntiles, m0 - off, mt, acc);
+                       tg, m0 - off, mt, acc);
     return hipGetLastError();
 }
 

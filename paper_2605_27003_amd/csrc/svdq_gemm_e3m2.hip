@@ -24,6 +24,7 @@
 #include "svdq_kernels.h"
 #include "svdq_lds.h"
 #include "svdq_quant_dev.h"
+#include "svdq_tiles.h"
 
 namespace svdq {
 
@@ -98,19 +99,13 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
                       const uint8_t* __restrict__ sfr,
                       const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
                       int64_t M, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
-                      int tile0, int mtiles, int ntiles, int64_t dm0, int dmt, int32_t* __restrict__ dacc,
+                      int tile0, const TileGrid tg, int64_t dm0, int dmt, int32_t* __restrict__ dacc,
                       const NextLayer nx) {
     constexpr bool DUMP = MODE == MODE_DUMP, NEXT = MODE >= MODE_NEXT, GELU = MODE == MODE_NEXT_GELU;
     __shared__ __attribute__((aligned(16))) uint8_t ring[NSLOTS * STAGE_BYTES];   // slot of group g: g % 5
 
-    // XCD-aware tile order: consecutive block ids go round-robin to the 8 XCDs, so give each XCD its own token
-    // tiles and walk them 8 at a time across n.
-    const int bid = blockIdx.x;
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int sm = idx / (8 * ntiles), rem = idx - sm * (8 * ntiles);
-    const int nt = rem >> 3;
-    const int mt = (sm * 8 + (rem & 7)) * 8 + xcd;
-    if (mt >= mtiles) return;
+    int mt, nt;                                 // XCD-aware tile order (svdq_tiles.h)
+    if (!tile_of(tg, blockIdx.x, mt, nt)) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -545,10 +540,6 @@ __global__ void zero_f32_kernel(float* __restrict__ p, int64_t n) {
     else for (int64_t j = i; j < n; ++j) p[j] = 0.f;
 }
 
-static inline unsigned grid_for(int mtiles, int ntiles) {
-    const int sms = (mtiles + 63) / 64;          // super-stripes of 8 XCDs x 8 token tiles
-    return (unsigned)(sms * 64 * ntiles);
-}
 
 }  // namespace
 
@@ -570,10 +561,11 @@ hipError_t launch_linear_e3m2(const uint8_t* act, const void* w_packed,
                               hipStream_t stream) {
     const int mtiles = (int)((M + BM - 1) / BM), ntiles = N / BN;
     const uint8_t* base = (const uint8_t*)w_packed;
-    hipLaunchKernelGGL(gemm_e3m2_kernel<MODE_LAYER>, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
+    const TileGrid tg = make_tile_grid(mtiles, ntiles);
+    hipLaunchKernelGGL(gemm_e3m2_kernel<MODE_LAYER>, dim3((unsigned)tile_ids(tg)), dim3(256), 0, stream,
                        act, base, base + w0_bytes(N, K), base + w0_bytes(N, K) + w1_bytes(N, K),
                        h, (const uint16_t*)L2, bias, M, N, K, r, y, ldy, out_f32,
-                       0, mtiles, ntiles, (int64_t)0, 0, (int32_t*)nullptr, NextLayer{});
+                       0, tg, (int64_t)0, 0, (int32_t*)nullptr, NextLayer{});
     return hipGetLastError();
 }
 
@@ -590,10 +582,11 @@ hipError_t launch_linear_e3m2_next(const uint8_t* act, const void* w_packed,
         hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, stream, next_h, n);
     }
     auto kern = gelu ? gemm_e3m2_kernel<MODE_NEXT_GELU> : gemm_e3m2_kernel<MODE_NEXT>;
-    hipLaunchKernelGGL(kern, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
+    const TileGrid tg = make_tile_grid(mtiles, ntiles);
+    hipLaunchKernelGGL(kern, dim3((unsigned)tile_ids(tg)), dim3(256), 0, stream,
                        act, base, base + w0_bytes(N, K), base + w0_bytes(N, K) + w1_bytes(N, K),
                        h, (const uint16_t*)L2, bias, M, N, K, r, (void*)nullptr, (int64_t)0, 0,
-                       0, mtiles, ntiles, (int64_t)0, 0, (int32_t*)nullptr, nx);
+                       0, tg, (int64_t)0, 0, (int32_t*)nullptr, nx);
     return hipGetLastError();
 }
 
@@ -603,11 +596,12 @@ hipError_t launch_group_acc_e3m2(const uint8_t* act, const void* w_packed, int64
     const int t0 = (int)(m0 / BM), t1 = (int)((m0 + mt + BM - 1) / BM);
     const int mtiles = t1 - t0, ntiles = N / BN;
     const uint8_t* base = (const uint8_t*)w_packed;
-    hipLaunchKernelGGL(gemm_e3m2_kernel<MODE_DUMP>, dim3(grid_for(mtiles, ntiles)), dim3(256), 0, stream,
+    const TileGrid tg = make_tile_grid(mtiles, ntiles);
+    hipLaunchKernelGGL(gemm_e3m2_kernel<MODE_DUMP>, dim3((unsigned)tile_ids(tg)), dim3(256), 0, stream,
                        act, base, base + w0_bytes(N, K), (const uint8_t*)nullptr,
                        (const float*)nullptr, (const uint16_t*)nullptr, (const float*)nullptr,
                        M, N, K, 0, (void*)nullptr, (int64_t)0, 0,
-                       t0, mtiles, ntiles, m0, mt, acc, NextLayer{});
+                       t0, tg, m0, mt, acc, NextLayer{});
     return hipGetLastError();
 }
 

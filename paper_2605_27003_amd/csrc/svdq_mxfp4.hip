@@ -22,6 +22,7 @@
 #include "svdq_epilogue.h"
 #include "svdq_kernels.h"
 #include "svdq_lds.h"
+#include "svdq_tiles.h"
 
 namespace svdq {
 
@@ -407,7 +408,7 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
                     const uint4* __restrict__ wfrag, const uint16_t* __restrict__ wscale,
                     const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
                     int64_t M, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
-                    int mtiles, int ntiles, const MxNext nx) {
+                    const TileGrid tg, const MxNext nx) {
     static_assert(MODE == MX_LAYER || WNC == 2, "the emitting epilogue is written for the four-wave geometry");
     using G = MxGeom<MT, WNC>;
     constexpr int BM = G::BM;
@@ -415,14 +416,8 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
     constexpr int NS = G::NS;
     __shared__ __attribute__((aligned(16))) uint8_t ring[NS * G::STAGE];
 
-    // XCD-aware tile order (consecutive block ids go round-robin to the 8 XCDs): each XCD walks its own
-    // token tiles, 8 at a time across n.
-    const int bid = blockIdx.x;
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int sm = idx / (8 * ntiles), rem = idx - sm * (8 * ntiles);
-    const int nt = rem >> 3;
-    const int mt = (sm * 8 + (rem & 7)) * 8 + xcd;
-    if (mt >= mtiles) return;
+    int mt, nt;                                 // XCD-aware tile order (svdq_tiles.h)
+    if (!tile_of(tg, blockIdx.x, mt, nt)) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -633,7 +628,7 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
                                const uint4* __restrict__ wfrag, const uint16_t* __restrict__ wscale,
                                const float* __restrict__ h, const uint16_t* __restrict__ L2, const float* __restrict__ bias,
                                int64_t M, int N, int K, int r, void* __restrict__ yout, int64_t ldy, int out_f32,
-                               int mtiles, int ntiles) {
+                               const TileGrid tg) {
     constexpr int WNC = 4;
     using G = MxGeom<MT, WNC>;
     constexpr int BM = G::BM, NDMA = G::NDMA, NS = 3;
@@ -649,19 +644,13 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
     const uint32_t ring0 = (uint32_t)(uintptr_t)(lds_byte*)ring;
     const uint32_t store0 = ring0 + NS * G::STAGE + wave * STORE_ROWS * YROW;
 
-    // tile ids: the one-tile kernel's decode of blockIdx.x
-    const int total = ((mtiles + 63) / 64) * 64 * ntiles;
-    auto decode = [&](const int id, int& mt, int& nt) {
-        const int xcd = id & 7, idx = id >> 3;
-        const int sm = idx / (8 * ntiles), rem = idx - sm * (8 * ntiles);
-        nt = rem >> 3;
-        mt = (sm * 8 + (rem & 7)) * 8 + xcd;
-    };
+    // tile ids: the one-tile kernel's order (svdq_tiles.h), of which this block takes ids b, b + gridDim, ...
+    const int total = tile_ids(tg);
+    auto decode = [&](const int id, int& mt, int& nt) { return tile_of(tg, id, mt, nt); };
     auto next_valid = [&](int id) {
         for (id += gridDim.x; id < total; id += gridDim.x) {
             int mt, nt;
-            decode(id, mt, nt);
-            if (mt < mtiles) return id;
+            if (decode(id, mt, nt)) return id;
         }
         return -1;
     };
@@ -749,8 +738,7 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
     int id = blockIdx.x;
     {
         int mt, nt;
-        decode(id, mt, nt);
-        if (mt >= mtiles) id = next_valid(id);
+        if (!decode(id, mt, nt)) id = next_valid(id);
     }
     if (id < 0) return;
     TileAddr T = tile_addr(id);
@@ -889,22 +877,20 @@ hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w
     const uint8_t* base = (const uint8_t*)w_packed;
     const uint16_t* wsc = (const uint16_t*)(base + mx_wfrag_bytes(N, K));
     const int mtiles = (int)((M + 64 * MT - 1) / (64 * MT));
-    const int sms = (mtiles + 63) / 64;
     if (walks_tiles(mtiles, N, K)) {         // 256 x 256 block tiles, eight waves, one block per CU walking its tiles
-        const int ntiles = N / 256;
         hipLaunchKernelGGL((gemm_mx_persistent_kernel<MT>), dim3(256), dim3(512), 0, stream,
                            qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
-                           M, N, K, r, y, ldy, out_f32, mtiles, ntiles);
+                           M, N, K, r, y, ldy, out_f32, make_tile_grid(mtiles, N / 256));
     } else if (N % 256 == 0) {               // 256 x 256 block tiles, eight waves, one block per CU and tile
-        const int ntiles = N / 256;
-        hipLaunchKernelGGL((gemm_mx_kernel<MT, 4, MX_LAYER>), dim3((unsigned)(sms * 64 * ntiles)), dim3(512), 0, stream,
+        const TileGrid tg = make_tile_grid(mtiles, N / 256);
+        hipLaunchKernelGGL((gemm_mx_kernel<MT, 4, MX_LAYER>), dim3((unsigned)tile_ids(tg)), dim3(512), 0, stream,
                            qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
-                           M, N, K, r, y, ldy, out_f32, mtiles, ntiles, MxNext{});
+                           M, N, K, r, y, ldy, out_f32, tg, MxNext{});
     } else {                                 // 256 x 128 block tiles, four waves, two blocks per CU
-        const int ntiles = N / 128;
-        hipLaunchKernelGGL((gemm_mx_kernel<MT, 2, MX_LAYER>), dim3((unsigned)(sms * 64 * ntiles)), dim3(256), 0, stream,
+        const TileGrid tg = make_tile_grid(mtiles, N / 128);
+        hipLaunchKernelGGL((gemm_mx_kernel<MT, 2, MX_LAYER>), dim3((unsigned)tile_ids(tg)), dim3(256), 0, stream,
                            qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
-                           M, N, K, r, y, ldy, out_f32, mtiles, ntiles, MxNext{});
+                           M, N, K, r, y, ldy, out_f32, tg, MxNext{});
     }
     return hipGetLastError();
 }
@@ -924,17 +910,16 @@ hipError_t launch_linear_mx_next(const uint8_t* qx, const uint8_t* sxe, const vo
     const uint8_t* base = (const uint8_t*)w_packed;
     const uint16_t* wsc = (const uint16_t*)(base + mx_wfrag_bytes(N, K));
     const int mtiles = (int)((M + 64 * MT - 1) / (64 * MT));
-    const int sms = (mtiles + 63) / 64;
-    const int ntiles = N / 128;
+    const TileGrid tg = make_tile_grid(mtiles, N / 128);
     const MxNext nx{next_inv_lambda, (const uint4*)next_l1p, next_qx, next_sxe, next_h, next_rho, next_l1p ? next_r : 0};
     if (nx.r > 0) {                                             // the tiles ADD their shares of h'
         const int64_t n = M * next_r;
         hipLaunchKernelGGL(zero_f32_mx_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, stream, next_h, n);
     }
     auto kern = gelu ? gemm_mx_kernel<MT, 2, MX_NEXT_GELU> : gemm_mx_kernel<MT, 2, MX_NEXT>;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(sms * 64 * ntiles)), dim3(256), 0, stream,
+    hipLaunchKernelGGL(kern, dim3((unsigned)tile_ids(tg)), dim3(256), 0, stream,
                        qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
-                       M, N, K, r, (void*)nullptr, (int64_t)0, 0, mtiles, ntiles, nx);
+                       M, N, K, r, (void*)nullptr, (int64_t)0, 0, tg, nx);
     return hipGetLastError();
 }
 

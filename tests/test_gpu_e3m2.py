@@ -76,7 +76,9 @@ def test_c1_full_layer(svdq, oracle, rho):
 
 
 @pytest.mark.parametrize("M,K,N,r", [(333, 1024, 256, 32), (130, 192, 128, 16), (1, 64, 128, 16), (2, 128, 128, 0),
-                                     (3, 320, 128, 32), (127, 5120, 384, 32), (200, 2048, 128, 0), (261, 256, 256, 16)])
+                                     (3, 320, 128, 32), (127, 5120, 384, 32), (200, 2048, 128, 0), (261, 256, 256, 16),
+                                     # few token tiles, many channel tiles: the channel-major tile order
+                                     (333, 256, 1024, 32), (1200, 192, 2048, 16)])
 def test_ragged_shapes(svdq, oracle, M, K, N, r):
     """Token counts around the row padding of the operand buffer (multiples of 4) and the 128-token tile, group
     counts below, at and above the depth of the staging ring (1, 2, 3, 4, 5, 16, 32, 80 groups)."""

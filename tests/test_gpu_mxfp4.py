@@ -69,7 +69,9 @@ def test_c1_full_layer(svdq, oracle, rho):
 
 
 @pytest.mark.parametrize("M,K,N,r", [(333, 1024, 256, 32), (130, 192, 128, 16), (1, 64, 128, 16),
-                                      (257, 448, 384, 0), (700, 2048, 128, 32)])
+                                      (257, 448, 384, 0), (700, 2048, 128, 32),
+                                      # few token tiles, many channel tiles: the channel-major tile order (both geometries)
+                                      (333, 256, 2048, 32), (700, 192, 1152, 16)])
 def test_ragged_shapes(svdq, oracle, M, K, N, r):
     x, L = small_layer(7, M, K, N, r)
     run_layer(svdq, oracle, x, L, 0.8, f"M={M} K={K} N={N} r={r}")

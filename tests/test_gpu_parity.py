@@ -79,7 +79,9 @@ def test_c1_full_layer(svdq, oracle, rho):
 
 
 @pytest.mark.parametrize("M,K,N,r", [(333, 1024, 256, 32), (130, 192, 128, 16), (1, 64, 128, 16),
-                                     (127, 5120, 384, 32), (200, 2048, 128, 0)])
+                                     (127, 5120, 384, 32), (200, 2048, 128, 0),
+                                     # few token tiles, many channel tiles: the channel-major tile order
+                                     (333, 256, 1024, 32), (1200, 192, 2048, 16)])
 def test_ragged_shapes(svdq, oracle, M, K, N, r):
     x, L = small_layer(7 + M, M, K, N, r)
     DL = DeviceLayer(L)
