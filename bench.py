@@ -80,7 +80,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the path shards by token rows with no exchange step "
-              "(see DESIGN.md), so --gpus N>1 is not implemented", file=sys.stderr)
+              "so --gpus N>1 is not implemented", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -23,7 +23,8 @@ T0 = time.time()
 
 
 def progress(msg):
-    """One line per finished step, also into gpurun_out/ when it exists (long steps must not look hung)."""
+    """One line per finished step, also appended to a log in the run's output folder when there is one (long steps
+    must not look hung)."""
     line = f"[{time.time() - T0:7.1f}s] {msg}"
     print(line, flush=True)
     d = os.path.join(ROOT, "gpurun_out")
