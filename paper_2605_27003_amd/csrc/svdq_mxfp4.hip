@@ -863,10 +863,25 @@ hipError_t launch_quantize_mx(const void* x, int64_t ldx, const float* inv_lambd
                 : launch_quantize_mx_any<false>(x, ldx, inv_lambda, rho, l1p, M, K, r, qx, sxe, h, stream);
 }
 
-// the tile-walking kernel needs full 256-channel tiles, a K loop longer than its ring, and pays once every CU has
-// at least two tiles
+// compute units of the current device (256 on MI355X; fewer in a partitioned mode), cached per device
+static int cu_count() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+// the tile-walking kernel runs one block per CU (a multiple of 8 blocks, so that a block stays on one XCD's share of
+// the tile order); it needs full 256-channel tiles, a K loop longer than its ring, and pays once every block has at
+// least two tiles
+static inline int walking_blocks() { return cu_count() / 8 * 8; }
 static inline bool walks_tiles(int mtiles, int N, int K) {
-    return N % 256 == 0 && K >= 512 && (int64_t)mtiles * (N / 256) >= 2 * 256;
+    return N % 256 == 0 && K >= 512 && (int64_t)mtiles * (N / 256) >= 2 * walking_blocks();
 }
 
 hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w_packed,
@@ -878,7 +893,7 @@ hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w
     const uint16_t* wsc = (const uint16_t*)(base + mx_wfrag_bytes(N, K));
     const int mtiles = (int)((M + 64 * MT - 1) / (64 * MT));
     if (walks_tiles(mtiles, N, K)) {         // 256 x 256 block tiles, eight waves, one block per CU walking its tiles
-        hipLaunchKernelGGL((gemm_mx_persistent_kernel<MT>), dim3(256), dim3(512), 0, stream,
+        hipLaunchKernelGGL((gemm_mx_persistent_kernel<MT>), dim3((unsigned)walking_blocks()), dim3(512), 0, stream,
                            qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
                            M, N, K, r, y, ldy, out_f32, make_tile_grid(mtiles, N / 256));
     } else if (N % 256 == 0) {               // 256 x 256 block tiles, eight waves, one block per CU and tile
