@@ -39,7 +39,8 @@ constexpr uint32_t OFF_W0 = 6144;      // weight fragments, bytes 0..15:  [n-blo
 constexpr uint32_t OFF_W1 = 10240;     // weight fragments, bytes 16..23: [n-block][lane] x 8 B
 constexpr uint32_t OFF_SFR = 12288;    // n-side operand of the scale-product MFMA: [n-block][channel] x 8 B
 constexpr uint32_t OFF_SXP = 13312;    // m-side operand: [token] x 8 B
-constexpr uint32_t STAGE_BYTES = 14336;
+constexpr uint32_t OFF_ZERO = 14336;   // 512 B of zeros, written once per block: the scale-product operands of k half 1
+constexpr uint32_t STAGE_BYTES = 14848;
 constexpr int NSLOTS = 5;
 
 typedef int int8v __attribute__((ext_vector_type(8)));
@@ -171,8 +172,13 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
     const uint32_t rd_x1 = OFF_A1 + (uint32_t)(kh * BM + wm * 64 + l32) * 8;       // + mi 256
     const uint32_t rd_w0 = OFF_W0 + (uint32_t)(wn * 2 * 64 + lane) * 16;           // + ni 1024
     const uint32_t rd_w1 = OFF_W1 + (uint32_t)(wn * 2 * 64 + lane) * 8;            // + ni 512
-    const uint32_t rd_sf = OFF_SFR + (uint32_t)(wn * 2 * 32 + l32) * 8;            // + ni 256
-    const uint32_t rd_sx = OFF_SXP + (uint32_t)(wm * 64 + l32) * 8;                // + mi 256
+    // The scale product needs K = 4 of the matrix instruction's 8: the lanes of k half 1 read zeros on both sides (an
+    // area of every slot that no transfer touches).  Multipliers fed 0 x 0 switch nothing, which on this power-limited
+    // chip is worth 1 % of the kernel's time against feeding both halves half the scale.
+    const uint32_t rd_sf = kh ? OFF_ZERO + (uint32_t)l32 * 8 : OFF_SFR + (uint32_t)(wn * 2 * 32 + l32) * 8;   // + ni 256
+    const uint32_t rd_sx = kh ? OFF_ZERO + (uint32_t)l32 * 8 : OFF_SXP + (uint32_t)(wm * 64 + l32) * 8;       // + mi 256
+    if (!DUMP && tid < 32 * NSLOTS)                      // visible after the barrier that ends the prologue
+        *reinterpret_cast<uint4*>(ring + (tid >> 5) * STAGE_BYTES + OFF_ZERO + (tid & 31) * 16) = uint4{0u, 0u, 0u, 0u};
 
     float16v y[2][2];                        // [ni][mi]
 #pragma unroll
@@ -232,7 +238,7 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         const int8v b = {(int)o.xlo[mi].x, (int)o.xlo[mi].y, (int)o.xlo[mi].z, (int)o.xlo[mi].w, (int)o.xhi[mi].x, (int)o.xhi[mi].y, 0, 0};
         return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, zero16, 3, 3, 0, 0x7f, 0, 0x7f);
     };
-    // S[n][m] = sw[n] sx[m]: n side {w1, w1, w2, w2} / 2 in both k halves, m side {x1, x2, x1, x2}
+    // S[n][m] = sw[n] sx[m]: n side {w1, w1, w2, w2}, m side {x1, x2, x1, x2} in k half 0, zeros in k half 1
     auto smma = [&](const Operands& o, const int ni, const int mi) -> float16v {
         if (DUMP) return zero16;
         return __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4v, o.sf[ni]),
@@ -469,8 +475,8 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
 // Region 1: bytes 0..15 of the weight fragments, [N/32][K/64][64 lanes][16 B]; region 2: bytes 16..23,
 // [N/32][K/64][64 lanes][8 B]: lane (n = lane % 32, kh = lane / 32) holds the E3M2 fields of k = 64 g + 32 kh + 0..31
 // of channel n, k ascending from bit 0.  Region 3: n-side operands of the scale-product MFMA,
-// [N/32][K/64][32 channels][8 B]: bf16 {w1, w1, w2, w2} / 2 with w1 + w2 ~ sw[g][n] (both k halves of that MFMA
-// read the same entry, hence the 1/2).
+// [N/32][K/64][32 channels][8 B]: bf16 {w1, w1, w2, w2} with w1 + w2 ~ sw[g][n] (the lanes of k half 0 read the
+// entry; those of k half 1 read zeros).
 __global__ void pack_weight_e3m2_kernel(const uint8_t* __restrict__ qw, const float* __restrict__ sw,
                                         int N, int K, uint8_t* __restrict__ out) {
     const int ng = K >> 6;
@@ -502,7 +508,7 @@ __global__ void pack_weight_e3m2_kernel(const uint8_t* __restrict__ qw, const fl
         const int l = (int)(v & 31);
         const size_t fr = v >> 5;
         const int g = (int)(fr % ng), nb = (int)(fr / ng);
-        const uint32_t p = split_bf16(0.5f * sw[(size_t)g * N + nb * 32 + l]);
+        const uint32_t p = split_bf16(sw[(size_t)g * N + nb * 32 + l]);
         const uint32_t w1 = p & 0xffffu, w2 = p >> 16;
         o3[v] = uint2{w1 | (w1 << 16), w2 | (w2 << 16)};
     }
