@@ -277,3 +277,70 @@ def test_mx_argument_errors(svdq):
     assert bad(16, None) == INV and bad(17, None) == INV and bad(12, 0.0) == INV and bad(12, float("nan")) == INV
     assert bad(7, 192) == SHAPE and bad(8, 100) == SHAPE and bad(14, 8) == SHAPE and bad(11, a + 4) == SHAPE
     assert bad(6, 0) == 0
+
+
+def test_graph_capture_of_the_emitting_epilogues(svdq):
+    """Both emitting entry points inside a HIP graph: the next layer's low-rank input is cleared by a kernel of the
+    call itself (not by a memset node), so replays, with eager work and synchronisations between them, reproduce
+    the eager operands byte for byte and h' up to summation order."""
+    M, K, N, r, r2 = 300, 512, 256, 32, 32
+    x, cm = synth.make_x(21, M, K, outlier_count=3, outlier_scale=30.0)
+    L1 = synth.make_layer(21, K, N, r, cm)
+    L1m = synth.make_layer(21, K, N, r, cm, fmt="mxfp4")
+    L2 = next_layer(9, N, r2)
+    D1 = DeviceLayer(L1)
+    wpm = svdq.pack_weight_mxfp4(dev(L1m.qw), dev(L1m.sw))
+    il2 = dev(L2.inv_lambda)
+    l1p2 = svdq.pack_lowrank_down(dev(L2.L1), il2)
+    xt = [dev(x), dev(np.roll(x, 7, axis=0))]
+    xin = torch.empty_like(xt[0])
+    act = svdq.ActE3M2(torch.empty(svdq.act_e3m2_bytes(M, K), dtype=torch.uint8, device="cuda"), M, K)
+    qx = torch.empty((K // 64, M, 32), dtype=torch.uint8, device="cuda")
+    sxm = torch.empty((K // 128, M, 2, 2), dtype=torch.uint8, device="cuda")
+    h = torch.empty((M, r), dtype=torch.float32, device="cuda")
+    out6, outm = zeroed_out(svdq, M, N, r2), mx_zeroed_out(M, N, r2)
+
+    def step():
+        svdq.quantize_act_e3m2(xin, D1.inv_lambda, 0.9, D1.l1p, r, out=(act, None, h))
+        svdq.linear_w4a4_e3m2_next(act, D1.wp6, N, il2, 0.8, h, D1.L2, D1.bias, gelu=True, next_l1_packed=l1p2,
+                                   next_r=r2, out=out6)
+        svdq.quantize_act_mxfp4(xin, D1.inv_lambda, 0.9, D1.l1p, r, out=(qx, sxm, h))
+        svdq.linear_mxfp4_next(qx, sxm, wpm, N, il2, 0.8, h, D1.L2, D1.bias, gelu=True, next_l1_packed=l1p2,
+                               next_r=r2, out=outm)
+
+    def snapshot():
+        return (out6[0].buf.clone(), out6[1].clone(), out6[2].clone(), outm[0].clone(), outm[1].clone(), outm[2].clone())
+
+    eager = []
+    for xv in xt:
+        xin.copy_(xv)
+        step()
+        torch.cuda.synchronize()
+        eager.append(snapshot())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        xin.copy_(xt[0])
+        step()
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        xin.copy_(xt[rep % 2])
+        for t in (out6[0].buf, out6[1], outm[0], outm[1]):
+            t.zero_()
+        out6[2].fill_(5.0)                                    # stale values the call must clear itself
+        outm[2].fill_(5.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got, want = snapshot(), eager[rep % 2]
+        for i in (0, 1, 3, 4):
+            assert torch.equal(got[i], want[i]), (rep, i)
+        for i in (2, 5):
+            assert float((got[i].double() - want[i].double()).norm() / want[i].double().norm()) <= 1e-6, (rep, i)
+        xin.copy_(xt[(rep + 1) % 2])                          # eager work between the replays
+        step()
+        torch.cuda.synchronize()
