@@ -462,24 +462,20 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
                                         : reinterpret_cast<const uint8_t*>(wscale + (size_t)(nbB + 2 * swp) * nstages * 64);
     const size_t sc_stride = (wave < 4) ? (size_t)M * 4 : (size_t)128;
     const uint32_t sc_lds = (wave < 4) ? G::OFF_SX + sxw * 256 : G::OFF_SW + swp * 256;
+    // transfer p (0 .. NDMA - 1) of this wave for stage s; always requested in this order.  Eight waves: the one scale
+    // transfer's base, stride and destination were chosen before the loop, so it needs no wave-dependent branch.
+    auto stage_piece = [&](const int s, const uint32_t slot, const int p) {
+        const int g = (2 * s + cj < ng) ? 2 * s + cj : ng - 1;        // odd tail: re-read (its scale bytes are zero)
+        if (p < NA) dma16(qx + (size_t)g * M * 32, va[p], slot + G::OFF_A + ((cj * 2 + sp) * BM + (q0 + p) * 64) * 16);
+        else if (p < NA + 2) dma16(wfrag + ((size_t)nbB * ng + g) * 64, vw[p - NA], slot + G::OFF_W + (cj * 2 * WNC + nb0 + p - NA) * 1024);
+        else if (WNC == 4) dma4(sc_base + (size_t)s * sc_stride, vsc, slot + sc_lds);
+        else if (p == NA + 2) dma4(sxe + (size_t)s * M * 2, vsx, slot + G::OFF_SX + sxw * 256);
+        else dma4(wscale + ((size_t)(nbB + 2 * swp) * nstages + s) * 64, vsw, slot + G::OFF_SW + swp * 256);
+    };
     auto stage_issue = [&](const int s) {
         const uint32_t slot = ring0 + (uint32_t)(s % NS) * G::STAGE;
-        const int g = (2 * s + cj < ng) ? 2 * s + cj : ng - 1;        // odd tail: re-read (its scale bytes are zero)
 #pragma unroll
-        for (int q = 0; q < NA; ++q)
-            dma16(qx + (size_t)g * M * 32, va[q], slot + G::OFF_A + ((cj * 2 + sp) * BM + (q0 + q) * 64) * 16);
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            dma16(wfrag + ((size_t)nbB * ng + g) * 64, vw[i], slot + G::OFF_W + (cj * 2 * WNC + nb0 + i) * 1024);
-        if (WNC == 2) {
-            dma4(sxe + (size_t)s * M * 2, vsx, slot + G::OFF_SX + sxw * 256);
-            dma4(wscale + ((size_t)(nbB + 2 * swp) * nstages + s) * 64, vsw, slot + G::OFF_SW + swp * 256);
-        } else {
-            // one scale transfer per wave; base, stride and destination were chosen before the loop, so there is no
-            // branch here (a branch splits the stage into basic blocks and the compiler then sinks the first
-            // group's matrix instructions past the barrier)
-            dma4(sc_base + (size_t)s * sc_stride, vsc, slot + sc_lds);
-        }
+        for (int p = 0; p < NDMA; ++p) stage_piece(s, slot, p);
     };
 
     // per-lane LDS read offsets inside a slot
@@ -547,23 +543,56 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
         }
     };
 
+    // The eight matrix instructions of a group carry, between them, the LDS reads of the OTHER operand set (two per
+    // instruction) and, in a stage's second group, the slot's new transfer requests (one each).  Requested as a burst
+    // ahead of a group they are time in which the matrix pipe has nothing queued: the waves of a block run in step.
+    auto mma_with_fetch = [&](const Operands& o, auto JC, Operands& on, const uint32_t slot, const int jn, auto request) {
+        constexpr int j = decltype(JC)::value;
+        auto one = [&](auto TC) {
+            constexpr int t = decltype(TC)::value, ni = t / MT, mi = t % MT;
+            const int8v a = {(int)o.wf[ni].x, (int)o.wf[ni].y, (int)o.wf[ni].z, (int)o.wf[ni].w, 0, 0, 0, 0};
+            const int8v b = {(int)o.xf[mi].x, (int)o.xf[mi].y, (int)o.xf[mi].z, (int)o.xf[mi].w, 0, 0, 0, 0};
+            y[ni][mi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, y[ni][mi], 4, 4, j, (int)o.sw[ni], j, (int)o.sx[mi]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (t < NDMA) request(t);
+            if (t < 2) {
+                on.wf[t] = lds_read16_pinned(slot + rd_w + jn * 2048 * WNC + t * 1024);
+                on.sw[t] = lds_read2_pinned(slot + rd_sw + t * 128);
+            } else if (t < 2 + MT) {
+                on.xf[t - 2] = lds_read16_pinned(slot + rd_a + jn * 32 * BM + (t - 2) * 512);
+                on.sx[t - 2] = lds_read2_pinned(slot + rd_sx + (t - 2) * 128);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        static_assert(MT == 4 && NDMA <= 8, "eight instructions per group");
+        one(IC<0>{}); one(IC<1>{}); one(IC<2>{}); one(IC<3>{});
+        one(IC<4>{}); one(IC<5>{}); one(IC<6>{}); one(IC<7>{});
+    };
+
     // One stage.  FULL: stages s+1..s+NS exist, so the body is straight-line code (the compiler otherwise sinks
     // the first group's matrix instructions past the conditional blocks, next to the second group's).
     auto stage_body = [&](const int s, const uint32_t cur, const uint32_t nxt, auto FULLC) {
         constexpr bool FULL = decltype(FULLC)::value;
-        // second group's operands requested, first group multiplied
+        if (FULL) {
+            // first group multiplied while the second group's operands are requested: after it this wave has
+            // requested everything it needs from the slot (the barrier waits for the loads to return), so after the
+            // barrier the slot can take stage s + NS; stage s + 1, requested NS - 1 stages ago, is made visible for
+            // the reads of the second group's instructions (stages s + 2 .. s + NS - 1 may stay in flight)
+            mma_with_fetch(op0, IC<0>{}, op1, cur, 1, [](int) {});
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NDMA) : "memory");
+            __syncthreads();
+            mma_with_fetch(op1, IC<1>{}, op0, nxt, 0, [&](const int p) { stage_piece(s + NS, cur, p); });
+            return;
+        }
+        // the last stages, with their conditions
         fetch(op1, cur, 1);
         __builtin_amdgcn_sched_barrier(0);
         mma_group(op0, IC<0>{});
         __builtin_amdgcn_sched_barrier(0);
-        // This wave has now requested everything it needs from the slot (the barrier waits for the loads to
-        // return), so after the barrier the slot can take stage s + NS; stage s + 1, requested NS - 1 stages ago,
-        // is made visible for the fetch below (stages s + 2 .. s + NS - 1 may stay in flight).
-        if (FULL || s + 1 < nstages) {
-            if (FULL) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NDMA) : "memory");
-            else wait_stages((nstages - 1 < s + NS - 1 ? nstages - 1 : s + NS - 1) - (s + 1));
+        if (s + 1 < nstages) {
+            wait_stages((nstages - 1 < s + NS - 1 ? nstages - 1 : s + NS - 1) - (s + 1));
             __syncthreads();
-            if (FULL || s + NS < nstages) stage_issue(s + NS);
+            if (s + NS < nstages) stage_issue(s + NS);
             fetch(op0, nxt, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -687,15 +716,16 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
                                : reinterpret_cast<const uint8_t*>(wscale + (size_t)(t.nbB + 2 * swp) * nstages * 64);
         return t;
     };
-    auto stage_issue = [&](const TileAddr& t, const int s, const uint32_t slot) {
+    // transfer p (0 .. NDMA - 1) of this wave for stage s of tile t; always requested in this order
+    auto stage_piece = [&](const TileAddr& t, const int s, const uint32_t slot, const int p) {
         const int g = (2 * s + cj < ng) ? 2 * s + cj : ng - 1;        // odd tail: re-read (its scale bytes are zero)
+        if (p < 2) dma16(qx + (size_t)g * M * 32, t.va[p], slot + G::OFF_A + ((cj * 2 + sp) * BM + (q0 + p) * 64) * 16);
+        else if (p < 4) dma16(wfrag + ((size_t)t.nbB * ng + g) * 64, vw[p - 2], slot + G::OFF_W + (cj * 2 * WNC + nb0 + p - 2) * 1024);
+        else dma4(t.sc_base + (size_t)s * sc_stride, t.vsc, slot + sc_lds);
+    };
+    auto stage_issue = [&](const TileAddr& t, const int s, const uint32_t slot) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
-            dma16(qx + (size_t)g * M * 32, t.va[q], slot + G::OFF_A + ((cj * 2 + sp) * BM + (q0 + q) * 64) * 16);
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            dma16(wfrag + ((size_t)t.nbB * ng + g) * 64, vw[i], slot + G::OFF_W + (cj * 2 * WNC + nb0 + i) * 1024);
-        dma4(t.sc_base + (size_t)s * sc_stride, t.vsc, slot + sc_lds);
+        for (int p = 0; p < NDMA; ++p) stage_piece(t, s, slot, p);
     };
 
     const uint32_t rd_a = G::OFF_A + (kh * BM + wm * (32 * MT) + l32) * 16;
@@ -777,20 +807,46 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
         __syncthreads();
         fetch(op0, cur, 0);
 
+        // The eight matrix instructions of a group carry the LDS reads of the OTHER operand set between them, two per
+        // instruction: both waves of a SIMD belong to this block and run in step, so a burst of twelve reads (or the
+        // five transfer requests) ahead of a group is time in which the matrix pipe has nothing queued.
+        auto mma_with_fetch = [&](const Operands& o, auto JC, Operands& on, const uint32_t slot, const int jn, const bool doit,
+                                  auto request) {
+            constexpr int j = decltype(JC)::value;
+            auto one = [&](auto TC) {
+                constexpr int t = decltype(TC)::value, ni = t / MT, mi = t % MT;
+                const int8v a = {(int)o.wf[ni].x, (int)o.wf[ni].y, (int)o.wf[ni].z, (int)o.wf[ni].w, 0, 0, 0, 0};
+                const int8v b = {(int)o.xf[mi].x, (int)o.xf[mi].y, (int)o.xf[mi].z, (int)o.xf[mi].w, 0, 0, 0, 0};
+                y[ni][mi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, y[ni][mi], 4, 4, j, (int)o.sw[ni], j, (int)o.sx[mi]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t < NDMA) request(t);
+                if (doit) {
+                    if (t < 2) {
+                        on.wf[t] = lds_read16_pinned(slot + rd_w + jn * 2048 * WNC + t * 1024);
+                        on.sw[t] = lds_read2_pinned(slot + rd_sw + t * 128);
+                    } else if (t < 2 + MT) {
+                        on.xf[t - 2] = lds_read16_pinned(slot + rd_a + jn * 32 * BM + (t - 2) * 512);
+                        on.sx[t - 2] = lds_read2_pinned(slot + rd_sx + (t - 2) * 128);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            static_assert(MT == 4 && NDMA <= 8, "eight instructions per group");
+            one(IC<0>{}); one(IC<1>{}); one(IC<2>{}); one(IC<3>{});
+            one(IC<4>{}); one(IC<5>{}); one(IC<6>{}); one(IC<7>{});
+        };
+        // Between the two groups of a stage stand only the wait and the barrier: the stage after this one is awaited
+        // and made visible, and this stage's slot is free (every read of it was requested during the first group).
+        // The second group's instructions then also carry the slot's new transfer requests, one each.
         auto stage_body = [&](const int s, const uint32_t c, const uint32_t nxt, auto SAMEC, auto ENDC) {
             constexpr bool SAME = decltype(SAMEC)::value, END = decltype(ENDC)::value;
-            fetch(op1, c, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            mma_group(op0, IC<0>{});
-            __builtin_amdgcn_sched_barrier(0);
+            mma_with_fetch(op0, IC<0>{}, op1, c, 1, true, [](int) {});
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NDMA) : "memory");
             __syncthreads();
-            if (SAME) stage_issue(T, s + NS, c);
-            else stage_issue(T1, s + NS - nstages, c);
-            if (!END) fetch(op0, nxt, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            mma_group(op1, IC<1>{});
-            __builtin_amdgcn_sched_barrier(0);
+            mma_with_fetch(op1, IC<1>{}, op0, nxt, 0, !END, [&](const int p) {
+                if (SAME) stage_piece(T, s + NS, c, p);
+                else stage_piece(T1, s + NS - nstages, c, p);
+            });
         };
         int s = 0;
         for (; s + NS < nstages; ++s) {
