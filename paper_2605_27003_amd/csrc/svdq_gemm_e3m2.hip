@@ -230,6 +230,24 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
             if (!DUMP) o.sf[ni] = lds_read8(slot + rd_sf + ni * 256);
         }
     };
+    // the same in two halves, for the loop: what the next group's first tile needs (token block 0, n-block 0), then
+    // the rest
+    auto fetch_half = [&](Operands& o, const uint32_t slot, const int hf) {
+        o.xlo[hf] = lds_read16_pinned(slot + rd_x0 + hf * 512);
+        o.xhi[hf] = lds_read8_pinned(slot + rd_x1 + hf * 256);
+        if (!DUMP) o.sxp[hf] = lds_read8_pinned(slot + rd_sx + hf * 256);
+        o.wlo[hf] = lds_read16_pinned(slot + rd_w0 + hf * 1024);
+        o.whi[hf] = lds_read8_pinned(slot + rd_w1 + hf * 512);
+        if (!DUMP) o.sf[hf] = lds_read8_pinned(slot + rd_sf + hf * 256);
+    };
+    auto stream_issue_part = [&](const uint32_t slot, const int i0, const int i1) {
+#pragma unroll
+        for (int i = i0; i < i1; ++i)
+            if (i < NDMA) {
+                dma16(sp[i], st[i].voff, slot + st[i].lds);
+                sp[i] += st[i].stride;
+            }
+    };
     fetch(op0, ring0);
 
     // exact integer sums of one tile and group: E3M2 x E3M2, block scales 2^0 (E8M0 127), C = 0
@@ -300,13 +318,17 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         PB = pmma(o, 0, 1);
         SB = smma(o, 0, 1);
         issued(PB, SB, y[0][0]);
-        if (FULL || g + 1 < ng) {
-            if (FULL) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
-            else wait_groups((ng - 1 < g + 3 ? ng - 1 : g + 3) - (g + 1));
+        const uint32_t prev = (cur == ring0) ? ring0 + (NSLOTS - 1) * STAGE_BYTES : cur - STAGE_BYTES;
+        if (FULL) {
+            // the twelve LDS reads and the four transfer requests of a group are spread over its steps 1..3, so that
+            // no step stands as a long run of memory instructions between two pairs of matrix instructions
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
             __syncthreads();
-            const uint32_t prev = (cur == ring0) ? ring0 + (NSLOTS - 1) * STAGE_BYTES : cur - STAGE_BYTES;
-            if (FULL) stream_issue(prev);
-            else if (g + 4 < ng) stage_issue(g + 4);
+            fetch_half(on, nxt, 0);
+        } else if (g + 1 < ng) {
+            wait_groups((ng - 1 < g + 3 ? ng - 1 : g + 3) - (g + 1));
+            __syncthreads();
+            if (g + 4 < ng) stage_issue(g + 4);
             fetch(on, nxt);
         }
         fold(PA, SA, y[0][0], g, 0, 0);
@@ -316,6 +338,10 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         PA = pmma(o, 1, 0);
         SA = smma(o, 1, 0);
         issued(PA, SA, y[0][1]);
+        if (FULL) {
+            fetch_half(on, nxt, 1);
+            stream_issue_part(prev, 0, 2);
+        }
         fold(PB, SB, y[0][1], g, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
 
@@ -323,6 +349,7 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         PB = pmma(o, 1, 1);
         SB = smma(o, 1, 1);
         issued(PB, SB, y[1][0]);
+        if (FULL) stream_issue_part(prev, 2, 4);
         fold(PA, SA, y[1][0], g, 1, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
