@@ -230,12 +230,13 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
             if (!DUMP) o.sf[ni] = lds_read8(slot + rd_sf + ni * 256);
         }
     };
-    // the same in two halves, for the loop: what the next group's first tile needs (token block 0, n-block 0), then
-    // the rest
-    auto fetch_half = [&](Operands& o, const uint32_t slot, const int hf) {
+    // the same in four parts, for the loop: the token side and the channel side of tile block hf
+    auto fetch_x = [&](Operands& o, const uint32_t slot, const int hf) {
         o.xlo[hf] = lds_read16_pinned(slot + rd_x0 + hf * 512);
         o.xhi[hf] = lds_read8_pinned(slot + rd_x1 + hf * 256);
         if (!DUMP) o.sxp[hf] = lds_read8_pinned(slot + rd_sx + hf * 256);
+    };
+    auto fetch_w = [&](Operands& o, const uint32_t slot, const int hf) {
         o.wlo[hf] = lds_read16_pinned(slot + rd_w0 + hf * 1024);
         o.whi[hf] = lds_read8_pinned(slot + rd_w1 + hf * 512);
         if (!DUMP) o.sf[hf] = lds_read8_pinned(slot + rd_sf + hf * 256);
@@ -305,26 +306,31 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         constexpr int SET = decltype(SETC)::value;
         const Operands& o = SET ? op1 : op0;
         Operands& on = SET ? op0 : op1;
-        // step 0: tile (0,0); finishes tile (1,1) of the previous group
+        const uint32_t prev = (cur == ring0) ? ring0 + (NSLOTS - 1) * STAGE_BYTES : cur - STAGE_BYTES;
+        // step 0: tile (0,0); finishes tile (1,1) of the previous group.  Every wave took its operands of this group
+        // from `cur` a group ago and of the previous group before that, so after the barrier the previous group's
+        // slot can take group g + 4; group g + 1, requested three groups ago, is visible after the barrier.  Its
+        // twelve LDS reads and the four transfer requests are spread over the four steps (three reads and one
+        // request each): as one run of sixteen memory instructions in a single step they cost 5 % of the kernel.
         PA = pmma(o, 0, 0);
         SA = smma(o, 0, 0);
         issued(PA, SA, y[1][1]);
+        if (FULL) {
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
+            __syncthreads();
+            fetch_x(on, nxt, 0);
+            stream_issue_part(prev, 0, 1);
+        }
         fold(PB, SB, y[1][1], g - 1, 1, 1);
         __builtin_amdgcn_sched_barrier(0);
 
-        // step 1: tile (0,1).  Every wave took its operands of this group from `cur` a group ago and of the
-        // previous group before that, so after the barrier the previous group's slot can take group g + 4;
-        // group g + 1, requested three groups ago, is visible after the barrier and its operands are requested.
+        // step 1: tile (0,1)
         PB = pmma(o, 0, 1);
         SB = smma(o, 0, 1);
         issued(PB, SB, y[0][0]);
-        const uint32_t prev = (cur == ring0) ? ring0 + (NSLOTS - 1) * STAGE_BYTES : cur - STAGE_BYTES;
         if (FULL) {
-            // the twelve LDS reads and the four transfer requests of a group are spread over its steps 1..3, so that
-            // no step stands as a long run of memory instructions between two pairs of matrix instructions
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
-            __syncthreads();
-            fetch_half(on, nxt, 0);
+            fetch_w(on, nxt, 0);
+            stream_issue_part(prev, 1, 2);
         } else if (g + 1 < ng) {
             wait_groups((ng - 1 < g + 3 ? ng - 1 : g + 3) - (g + 1));
             __syncthreads();
@@ -339,8 +345,8 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         SA = smma(o, 1, 0);
         issued(PA, SA, y[0][1]);
         if (FULL) {
-            fetch_half(on, nxt, 1);
-            stream_issue_part(prev, 0, 2);
+            fetch_x(on, nxt, 1);
+            stream_issue_part(prev, 2, 3);
         }
         fold(PB, SB, y[0][1], g, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
@@ -349,7 +355,10 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         PB = pmma(o, 1, 1);
         SB = smma(o, 1, 1);
         issued(PB, SB, y[1][0]);
-        if (FULL) stream_issue_part(prev, 2, 4);
+        if (FULL) {
+            fetch_w(on, nxt, 1);
+            stream_issue_part(prev, 3, 4);
+        }
         fold(PA, SA, y[1][0], g, 1, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
