@@ -185,6 +185,28 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
         }
     };
 
+    // the same in three parts (3 + 2 + 2 transfers; 3 + 1 + 0 without the scale operands), for the main loop
+    auto stream_issue_part = [&](const uint32_t slot, const int part) {
+        if (part == 0) {
+            dma16(pa, va[0], slot + lds_a[0]);
+            dma16(pw, vw[0], slot + lds_w[0]);
+            dma16(pa, va[1], slot + lds_a[1]);
+        } else if (part == 1) {
+            dma16(pw, vw[1], slot + lds_w[1]);
+            if (!DUMP) dma16(pc, vl16, slot + OFF_CFR + wave * 1024);
+        } else {
+            if (!DUMP) {
+                dma16(ps, vsf, slot + OFF_SFR + (sfj * 4 + 2 * sfp) * 512);
+                dma4(px, vx, slot + raw_sx);
+                pc += 64;
+                ps += 128;
+                px += step_x;
+            }
+            pa += step_a;
+            pw += 128;
+        }
+    };
+
     // per-lane LDS read offsets inside a slot
     const uint32_t rd_a = OFF_A + (kh * BM + wm * 64 + l32) * 16;      // + group 4096 + mi 512
     const uint32_t rd_w = OFF_W + (wn * 2 * 64 + lane) * 16;           // + group 4096 + ni 1024
@@ -312,8 +334,17 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             if (!DUMP) scale_expand(s + 1, nxt, FULL);
             __syncthreads();
-            if (FULL) stream_issue(cur);
+            if (FULL) stream_issue_part(cur, 0);
             else if (s + 3 < nstages) stage_issue(s + 3);
+        }
+        // FULL: the next group's operands are requested as their registers fall free (the packed codes once they are
+        // unpacked, a scale operand after the last matrix instruction that reads it), two or four reads a step, and
+        // the stage's transfer requests in three parts, instead of eight reads and seven requests in one step each
+        const uint32_t src = (j == 0) ? cur : nxt;
+        constexpr uint32_t oa = (j == 0) ? 4096 : 0, osx = (j == 0) ? 1024 : 0, osf = (j == 0) ? 2048 : 0;
+        if (FULL) {
+            xpk[0] = lds_read16(src + rd_a + oa);
+            wpk[0] = lds_read16(src + rd_w + oa);
         }
         fold(acc0, S0, y[0][0], g, 0, 0);
         if (j == 0) corr(y[0][0], cn[0], cm[0]);
@@ -323,6 +354,11 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
         unpack16(wpk[1], wlo[1], whi[1]);
         acc0 = imma(wlo[1], whi[1], xlo[0], xhi[0]);
         S0 = smma(sfr[1], sxs[0]);
+        if (FULL) {
+            xpk[1] = lds_read16(src + rd_a + oa + 512);
+            if (!DUMP) sfr[0] = lds_read8(src + rd_sf + osf);
+            if (j == 1) stream_issue_part(cur, 1);
+        }
         fold(acc1, S1, y[0][1], g, 0, 1);
         if (j == 0) corr(y[0][1], cn[0], cm[1]);
         __builtin_amdgcn_sched_barrier(0);
@@ -330,9 +366,15 @@ void gemm_kernel(const uint8_t* __restrict__ qx, const float* __restrict__ sx,
         // step 3: tile (1,1); then the operands of the next group into the registers its MFMAs have just read
         accP = imma(wlo[1], whi[1], xlo[1], xhi[1]);
         SP = smma(sfr[1], sxs[1]);
-        if (FULL || g + 1 < ng) {
-            const uint32_t src = (j == 0) ? cur : nxt;
-            constexpr uint32_t oa = (j == 0) ? 4096 : 0, osx = (j == 0) ? 1024 : 0, osf = (j == 0) ? 2048 : 0;
+        if (FULL) {
+            wpk[1] = lds_read16(src + rd_w + oa + 1024);
+            if (!DUMP) {
+                sxs[0] = lds_read8(src + rd_sx + osx);
+                sxs[1] = lds_read8(src + rd_sx + osx + 256);
+                sfr[1] = lds_read8(src + rd_sf + osf + 512);
+            }
+            if (j == 1) stream_issue_part(cur, 2);
+        } else if (g + 1 < ng) {
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi) {
                 xpk[mi] = lds_read16(src + rd_a + oa + mi * 512);
