@@ -308,16 +308,21 @@ void gemm_e3m2_kernel(const uint8_t* __restrict__ act, const uint8_t* __restrict
         Operands& on = SET ? op0 : op1;
         const uint32_t prev = (cur == ring0) ? ring0 + (NSLOTS - 1) * STAGE_BYTES : cur - STAGE_BYTES;
         // step 0: tile (0,0); finishes tile (1,1) of the previous group.  Every wave took its operands of this group
-        // from `cur` a group ago and of the previous group before that, so after the barrier the previous group's
-        // slot can take group g + 4; group g + 1, requested three groups ago, is visible after the barrier.  Its
-        // twelve LDS reads and the four transfer requests are spread over the four steps (three reads and one
-        // request each): as one run of sixteen memory instructions in a single step they cost 5 % of the kernel.
+        // from `cur` a group ago, so the previous group's slot can take group g + 4.  The next group's twelve LDS
+        // reads and the four transfer requests are spread over the four steps (three reads and one request each):
+        // as one run of sixteen memory instructions in a single step they cost 5 % of the kernel.
         PA = pmma(o, 0, 0);
         SA = smma(o, 0, 0);
         issued(PA, SA, y[1][1]);
         if (FULL) {
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
-            __syncthreads();
+            // One barrier per PAIR of groups (operand set 0 = even group g): it waits until only group g + 3 is in
+            // flight, so groups g + 1 and g + 2, whose operands are read during g and g + 1, are visible to all
+            // waves; and every wave has finished its reads of slots g - 1 and g (issued during g - 2 and g - 1),
+            // which take groups g + 4 and g + 5 during this pair.
+            if (SET == 0) {
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NDMA) : "memory");
+                __syncthreads();
+            }
             fetch_x(on, nxt, 0);
             stream_issue_part(prev, 0, 1);
         }
