@@ -18,18 +18,17 @@ from workloads import synth
 from tests.helpers import DeviceLayer, check_y, dev, host_bits, rel_fro
 
 pytestmark = pytest.mark.gpu
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 T0 = time.time()
 
 
 def progress(msg):
-    """One line per finished step, also appended to a log in the run's output folder when there is one (long steps
-    must not look hung)."""
+    """One line per finished step, also appended to the file SVDQ_PROGRESS_LOG names when it is set (pytest holds
+    back stdout; a long step must not look hung)."""
     line = f"[{time.time() - T0:7.1f}s] {msg}"
     print(line, flush=True)
-    d = os.path.join(ROOT, "gpurun_out")
-    if os.path.isdir(d):
-        with open(os.path.join(d, "fullsize_progress.log"), "a") as f:
+    log = os.environ.get("SVDQ_PROGRESS_LOG")
+    if log:
+        with open(log, "a") as f:
             f.write(line + "\n")
 
 
