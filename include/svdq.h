@@ -49,12 +49,15 @@ extern "C" {
 typedef enum {
     SVDQ_OK = 0,
     SVDQ_ERR_INVALID_ARG = -1,        /* NULL required pointer, negative size, rho outside (0,1], bad enum */
-    SVDQ_ERR_UNSUPPORTED_SHAPE = -2,  /* K % 64, N % 128, r not in {0,16,32}, ld too small or misaligned */
+    SVDQ_ERR_UNSUPPORTED_SHAPE = -2,  /* K % 64, N % 128, r not in {0,16,32}, ld too small or misaligned, M > SVDQ_MAX_M */
     SVDQ_ERR_UNSUPPORTED_ARCH = -3,   /* current device is not gfx950 */
     SVDQ_ERR_HIP = -4                 /* a HIP runtime call or launch failed */
 } svdq_status;
 
 enum { SVDQ_GROUP = 64, SVDQ_N_TILE = 128, SVDQ_MAX_RANK = 32, SVDQ_MAX_K = 16384 };
+/* Largest token count of any kernel entry point (the kernels keep per-lane byte offsets into one group's block of
+ * the activation buffers in 32 bits); more rows are rejected with SVDQ_ERR_UNSUPPORTED_SHAPE before any launch. */
+#define SVDQ_MAX_M ((int64_t)1 << 26)
 enum { SVDQ_OUT_BF16 = 0, SVDQ_OUT_F32 = 1 };
 
 const char* svdq_status_string(int status);
@@ -314,11 +317,21 @@ int svdq_linear_mxfp4_next(const uint8_t* qx, const uint8_t* sx_e8m0, const void
  *   out[0] = sum_{m < M, n < N} (y_ref[m,n] - y[m,n])^2       (device binary64, deterministic)
  *   y_ref_bf16 [M, ld_ref], y_bf16 [M, ldy] bf16;  N % 8 == 0, leading dimensions % 8 == 0
  *   workspace  caller's device buffer of svdq_sq_error_workspace_bytes() bytes (partial sums)
- * M == 0 gives 0.  The arg-min over the handful of sums is left to the caller.
+ * M == 0 gives 0.
+ *   svdq_sq_error_add   the same sum ADDED to acc[0] (device binary64): the expectation over the calibration steps
+ *                       of a bin, accumulated on the device in stream order (deterministic).  The caller zeroes
+ *                       the table of accumulators [nbins][ncandidates] before the first step and passes the
+ *                       entry of (bin, candidate).
+ *   svdq_argmin_rows    idx[b] = index of the smallest entry of table[b][0..ncols) (the first one on a tie): the
+ *                       arg-min over the candidate set, per bin.  table, idx on the device; ncols >= 1.
  */
 size_t svdq_sq_error_workspace_bytes(void);
 int svdq_sq_error(const void* y_ref_bf16, int64_t ld_ref, const void* y_bf16, int64_t ldy,
                   int64_t M, int N, void* workspace, double* out, void* stream);
+int svdq_sq_error_add(const void* y_ref_bf16, int64_t ld_ref, const void* y_bf16, int64_t ldy,
+                      int64_t M, int N, void* workspace, double* acc, void* stream);
+int svdq_argmin_rows(const double* table, int nrows, int ncols, int32_t* idx, void* stream);
+
 
 /*
  * Test hook: the scalar part of kernel (a)'s chain, eq. 8-9, evaluated by the

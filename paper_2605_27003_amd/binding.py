@@ -45,6 +45,8 @@ EXPORTS = {
     "svdq_gptq_quantize": (_i32, [_vp, _vp, ctypes.c_double, _i32, _i32, _vp, _vp, _vp, _vp]),
     "svdq_sq_error_workspace_bytes": (ctypes.c_size_t, []),
     "svdq_sq_error": (_i32, [_vp, _i64, _vp, _i64, _i64, _i32, _vp, _vp, _vp]),
+    "svdq_sq_error_add": (_i32, [_vp, _i64, _vp, _i64, _i64, _i32, _vp, _vp, _vp]),
+    "svdq_argmin_rows": (_i32, [_vp, _i32, _i32, _vp, _vp]),
     "svdq_debug_group_acc": (_i32, [_vp, _vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp]),
     "svdq_debug_scale_chain": (_i32, [_vp, _f32, _i64, _vp, _vp, _vp]),
 }
@@ -237,11 +239,15 @@ def packed_weight_e3m2_bytes(N, K):
     return load_library().svdq_packed_weight_e3m2_bytes(N, K)
 
 
-def pack_weight_e3m2(qw, sw):
-    """qw [N,K/2] uint8 canonical codes, sw [K/64,N] f32 (device) -> opaque uint8 tensor for linear_w4a4_e3m2."""
+def pack_weight_e3m2(qw, sw, out=None):
+    """qw [N,K/2] uint8 canonical codes, sw [K/64,N] f32 (device) -> opaque uint8 tensor for linear_w4a4_e3m2.
+    `out`: a caller's buffer of at least packed_weight_e3m2_bytes(N, K) bytes (e.g. one staging buffer shared by
+    every layer of a model whose weights stay resident in the canonical 4-bit form)."""
     N, K2 = qw.shape
     K = 2 * K2
-    out = torch.empty(packed_weight_e3m2_bytes(N, K), dtype=torch.uint8, device=qw.device)
+    if out is None:
+        out = torch.empty(packed_weight_e3m2_bytes(N, K), dtype=torch.uint8, device=qw.device)
+    assert out.numel() >= packed_weight_e3m2_bytes(N, K)
     _check(load_library().svdq_pack_weight_e3m2(_ptr(qw), _ptr(sw), N, K, _ptr(out), _stream()), "svdq_pack_weight_e3m2")
     return out
 
@@ -439,19 +445,24 @@ def sq_error(y_ref, y, workspace=None, out=None):
 def search_clipping_ratios(layer_run, xs, y_refs, bins, nbins, candidates):
     """Timestep-bin clipping-ratio search.  `layer_run(x, rho)` runs the quantised layer (quantise + GEMM kernels)
     and returns y bf16; xs[i], y_refs[i] are the calibration input and full-precision output of step i, bins[i]
-    its timestep bin.  Returns (table [nbins] of chosen ratios, err [nbins][len(candidates)] summed errors)."""
+    its timestep bin.  Returns (table [nbins] of chosen ratios, err [nbins][len(candidates)] summed errors).
+    The sums over a bin's steps and the arg-min over the candidates run in the library, on the device."""
+    lib = load_library()
     dev = xs[0].device
-    ws = torch.empty(load_library().svdq_sq_error_workspace_bytes() // 8, dtype=torch.float64, device=dev)
-    acc = torch.zeros((nbins, len(candidates)), dtype=torch.float64, device=dev)
-    one = torch.empty(1, dtype=torch.float64, device=dev)
+    nc = len(candidates)
+    ws = torch.empty(lib.svdq_sq_error_workspace_bytes() // 8, dtype=torch.float64, device=dev)
+    acc = torch.zeros((nbins, nc), dtype=torch.float64, device=dev)
+    idx = torch.empty(nbins, dtype=torch.int32, device=dev)
     for x, yr, b in zip(xs, y_refs, bins):
+        M, N = yr.shape
         for ci, rho in enumerate(candidates):
             y = layer_run(x, rho)
-            sq_error(yr, y, ws, one)
-            acc[b, ci] += one[0]
-    err = acc.cpu().numpy()
-    table = [float(candidates[int(i)]) for i in err.argmin(axis=1)]
-    return table, err
+            _check(lib.svdq_sq_error_add(_ptr(yr), yr.stride(0) if M > 1 else N, _ptr(y), y.stride(0) if M > 1 else N,
+                                         M, N, _ptr(ws), ctypes.c_void_p(acc.data_ptr() + 8 * (b * nc + ci)), _stream()),
+                   "svdq_sq_error_add")
+    _check(lib.svdq_argmin_rows(_ptr(acc), nbins, nc, _ptr(idx), _stream()), "svdq_argmin_rows")
+    table = [float(candidates[i]) for i in idx.cpu().tolist()]
+    return table, acc.cpu().numpy()
 
 
 def debug_scale_chain(a, rho):

@@ -3,6 +3,7 @@
 // synchronisation.
 #include "svdq.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 
@@ -14,16 +15,18 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // SVDQ_OK when the current device is gfx950; cached per device index.
 int check_arch() {
-    static int cached[64];                         // 0 unknown, 1 ok, 2 unsupported
+    static std::atomic<int> cached[64];            // 0 unknown, 1 ok, 2 unsupported; any thread may call the library
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return SVDQ_ERR_HIP;
     if (dev < 0 || dev >= 64) return SVDQ_ERR_HIP;
-    if (cached[dev] == 0) {
+    int state = cached[dev].load(std::memory_order_relaxed);
+    if (state == 0) {
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return SVDQ_ERR_HIP;
-        cached[dev] = (std::strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : 2;
+        state = (std::strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : 2;
+        cached[dev].store(state, std::memory_order_relaxed);      // racing threads store the same value
     }
-    return cached[dev] == 1 ? SVDQ_OK : SVDQ_ERR_UNSUPPORTED_ARCH;
+    return state == 1 ? SVDQ_OK : SVDQ_ERR_UNSUPPORTED_ARCH;
 }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? SVDQ_OK : SVDQ_ERR_HIP; }
@@ -79,6 +82,7 @@ static int quantize_nibble(const void* x_bf16, int64_t ldx, const float* inv_lam
     if (!aligned16(x_bf16) || !aligned16(inv_lambda) || !aligned16(qx) || !aligned16(sx) ||
         !aligned16(l1_packed) || (l1_packed && !aligned16(h)))
         return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_quantize(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, qx, sx, h, gelu,
@@ -117,6 +121,7 @@ int svdq_linear_w4a4(const uint8_t* qx, const float* sx, const void* w_packed,
     if (!aligned16(qx) || !aligned16(sx) || !aligned16(w_packed) || !aligned16(h) || !aligned16(L2_bf16) ||
         !aligned16(bias) || !aligned16(y))
         return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_linear(qx, sx, w_packed, h, L2_bf16, bias, M, N, K, r, y, ldy,
@@ -136,6 +141,7 @@ int svdq_lowrank(int mode, const void* x_bf16, int64_t ldx, const float* inv_lam
         if (!y_bf16) return SVDQ_ERR_INVALID_ARG;
         if (N <= 0 || ldy < N) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     }
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     if (mode == 0)
@@ -148,6 +154,7 @@ int svdq_debug_group_acc(const uint8_t* qx, const void* w_packed, int64_t M, int
     if (!qx || !w_packed || !acc || M < 0 || m0 < 0 || mt < 0 || m0 + mt > M) return SVDQ_ERR_INVALID_ARG;
     if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (!aligned16(qx) || !aligned16(w_packed)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (mt == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_group_acc(qx, w_packed, M, N, K, m0, mt, acc, (hipStream_t)stream));
@@ -169,6 +176,7 @@ static int quantize_e3m2(const void* x_bf16, int64_t ldx, const float* inv_lambd
     if (!aligned16(x_bf16) || !aligned16(inv_lambda) || !aligned16(act) || !aligned16(sx) ||
         !aligned16(l1_packed) || (l1_packed && !aligned16(h)))
         return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_quantize_e3m2(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, act, sx, h, gelu,
@@ -185,6 +193,7 @@ int svdq_unpack_act_e3m2(const uint8_t* act, int64_t M, int K, uint8_t* qx, void
     if (!act || !qx || M < 0) return SVDQ_ERR_INVALID_ARG;
     if (K <= 0 || K % SVDQ_GROUP) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (!aligned16(act) || !aligned16(qx)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_unpack_act_e3m2(act, M, K, qx, (hipStream_t)stream));
@@ -216,6 +225,7 @@ int svdq_linear_w4a4_e3m2(const uint8_t* act, const void* w_packed,
     if (!aligned16(act) || !aligned16(w_packed) || !aligned16(h) || !aligned16(L2_bf16) ||
         !aligned16(bias) || !aligned16(y))
         return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_linear_e3m2(act, w_packed, h, L2_bf16, bias, M, N, K, r, y, ldy,
@@ -238,6 +248,7 @@ int svdq_linear_w4a4_e3m2_next(const uint8_t* act, const void* w_packed,
         !aligned16(next_inv_lambda) || !aligned16(next_l1_packed) || !aligned16(next_act) || !aligned16(next_sx) ||
         (next_l1_packed && !aligned16(next_h)))
         return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_linear_e3m2_next(act, w_packed, h, L2_bf16, bias, M, N, K, r, gelu != 0,
@@ -250,6 +261,7 @@ int svdq_debug_group_acc_e3m2(const uint8_t* act, const void* w_packed, int64_t 
     if (!act || !w_packed || !acc || M < 0 || m0 < 0 || mt < 0 || m0 + mt > M) return SVDQ_ERR_INVALID_ARG;
     if (N <= 0 || K <= 0 || K % SVDQ_GROUP || N % SVDQ_N_TILE) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (!aligned16(act) || !aligned16(w_packed)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (mt == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_group_acc_e3m2(act, w_packed, M, N, K, m0, mt, acc, (hipStream_t)stream));
@@ -266,6 +278,7 @@ static int quantize_mx(const void* x_bf16, int64_t ldx, const float* inv_lambda,
     if (!aligned16(x_bf16) || !aligned16(inv_lambda) || !aligned16(qx) || !aligned16(sx_e8m0) ||
         !aligned16(l1_packed) || (l1_packed && !aligned16(h)))
         return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_quantize_mx(x_bf16, ldx, inv_lambda, rho, l1_packed, M, K, r, qx, sx_e8m0, h, gelu,
@@ -326,6 +339,7 @@ int svdq_linear_mxfp4(const uint8_t* qx, const uint8_t* sx_e8m0, const void* w_p
     if (!aligned16(qx) || !aligned16(sx_e8m0) || !aligned16(w_packed) || !aligned16(h) || !aligned16(L2_bf16) ||
         !aligned16(bias) || !aligned16(y))
         return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_linear_mx(qx, sx_e8m0, w_packed, h, L2_bf16, bias, M, N, K, r, y, ldy,
@@ -348,6 +362,7 @@ int svdq_linear_mxfp4_next(const uint8_t* qx, const uint8_t* sx_e8m0, const void
         !aligned16(bias) || !aligned16(next_inv_lambda) || !aligned16(next_l1_packed) || !aligned16(next_qx) ||
         !aligned16(next_sx_e8m0) || (next_l1_packed && !aligned16(next_h)))
         return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_linear_mx_next(qx, sx_e8m0, w_packed, h, L2_bf16, bias, M, N, K, r, gelu != 0,
@@ -363,6 +378,7 @@ size_t svdq_gptq_workspace_bytes(int N, int K) {
 int svdq_gptq_hessian(const void* x_bf16, int64_t ldx, const float* inv_lambda, int64_t M, int K, double* H, void* stream) {
     if (!x_bf16 || !inv_lambda || !H || M < 0) return SVDQ_ERR_INVALID_ARG;
     if (K <= 0 || K % SVDQ_GROUP || ldx < K) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_MAX_M) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return SVDQ_OK;
     if (int a = check_arch()) return a;
     return hip_status(svdq::launch_gptq_hessian(x_bf16, ldx, inv_lambda, M, K, H, (hipStream_t)stream));
@@ -386,9 +402,27 @@ int svdq_sq_error(const void* y_ref_bf16, int64_t ld_ref, const void* y_bf16, in
     if (N <= 0 || N % 8 || ld_ref < N || ldy < N || ld_ref % 8 || ldy % 8) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (!aligned16(y_ref_bf16) || !aligned16(y_bf16) || !aligned16(workspace)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
     if (int a = check_arch()) return a;
-    return hip_status(svdq::launch_sq_error(y_ref_bf16, ld_ref, y_bf16, ldy, M, N, (double*)workspace, out,
+    return hip_status(svdq::launch_sq_error(y_ref_bf16, ld_ref, y_bf16, ldy, M, N, (double*)workspace, out, false,
                                             (hipStream_t)stream));
 }
+
+int svdq_sq_error_add(const void* y_ref_bf16, int64_t ld_ref, const void* y_bf16, int64_t ldy,
+                      int64_t M, int N, void* workspace, double* acc, void* stream) {
+    if (!y_ref_bf16 || !y_bf16 || !workspace || !acc || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || N % 8 || ld_ref < N || ldy < N || ld_ref % 8 || ldy % 8) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(y_ref_bf16) || !aligned16(y_bf16) || !aligned16(workspace)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_sq_error(y_ref_bf16, ld_ref, y_bf16, ldy, M, N, (double*)workspace, acc, true,
+                                            (hipStream_t)stream));
+}
+
+int svdq_argmin_rows(const double* table, int nrows, int ncols, int32_t* idx, void* stream) {
+    if (!table || !idx || nrows < 0 || ncols <= 0) return SVDQ_ERR_INVALID_ARG;
+    if (nrows == 0) return SVDQ_OK;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_argmin_rows(table, nrows, ncols, idx, (hipStream_t)stream));
+}
+
 
 int svdq_debug_scale_chain(const float* a, float rho, int64_t n, float* s, float* inv, void* stream) {
     if (!a || !s || !inv || n < 0 || n > (int64_t)1 << 31) return SVDQ_ERR_INVALID_ARG;

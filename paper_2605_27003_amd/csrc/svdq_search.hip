@@ -5,12 +5,16 @@
 //
 // Deterministic: NPART blocks each own a fixed, strided set of 8-element chunks and sum them in a fixed
 // order in binary64; a second one-block kernel adds the NPART partial sums in index order.
+//
+// Also here: the expectation over a bin's calibration steps (the same reduction ADDED to a device accumulator) and
+// the arg-min over the candidates, so that a C caller can run the whole search without host arithmetic.
 #include "svdq_dev.h"
 #include "svdq_kernels.h"
 
 namespace svdq {
 
 namespace {
+
 
 __global__ __launch_bounds__(256)
 void sq_error_partial_kernel(const uint16_t* __restrict__ yref, int64_t ldr, const uint16_t* __restrict__ y, int64_t ldy,
@@ -43,21 +47,42 @@ void sq_error_partial_kernel(const uint16_t* __restrict__ yref, int64_t ldr, con
     if (threadIdx.x == 0) partials[blockIdx.x] = red[0];
 }
 
+// ADD = true: out[0] += the sum (one thread, so the accumulation over calls on a stream is deterministic)
+template <bool ADD>
 __global__ void sq_error_final_kernel(const double* __restrict__ partials, int n, double* __restrict__ out) {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         double s = 0.0;
         for (int i = 0; i < n; ++i) s += partials[i];
-        out[0] = s;
+        out[0] = ADD ? out[0] + s : s;
     }
+}
+
+// idx[row] = first index of the smallest entry of table[row][0..ncols): one thread per row
+__global__ void argmin_rows_kernel(const double* __restrict__ table, int nrows, int ncols, int32_t* __restrict__ idx) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= nrows) return;
+    const double* t = table + (size_t)row * ncols;
+    int best = 0;
+    for (int c = 1; c < ncols; ++c)
+        if (t[c] < t[best]) best = c;
+    idx[row] = best;
 }
 
 }  // namespace
 
 hipError_t launch_sq_error(const void* yref, int64_t ldr, const void* y, int64_t ldy, int64_t M, int N,
-                           double* workspace, double* out, hipStream_t stream) {
+                           double* workspace, double* out, bool add, hipStream_t stream) {
     hipLaunchKernelGGL(sq_error_partial_kernel, dim3(SQ_ERROR_PARTIALS), dim3(256), 0, stream,
                        (const uint16_t*)yref, ldr, (const uint16_t*)y, ldy, M, N, workspace);
-    hipLaunchKernelGGL(sq_error_final_kernel, dim3(1), dim3(64), 0, stream, workspace, SQ_ERROR_PARTIALS, out);
+    if (add)
+        hipLaunchKernelGGL(sq_error_final_kernel<true>, dim3(1), dim3(64), 0, stream, workspace, SQ_ERROR_PARTIALS, out);
+    else
+        hipLaunchKernelGGL(sq_error_final_kernel<false>, dim3(1), dim3(64), 0, stream, workspace, SQ_ERROR_PARTIALS, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_argmin_rows(const double* table, int nrows, int ncols, int32_t* idx, hipStream_t stream) {
+    hipLaunchKernelGGL(argmin_rows_kernel, dim3((unsigned)((nrows + 63) / 64)), dim3(64), 0, stream, table, nrows, ncols, idx);
     return hipGetLastError();
 }
 

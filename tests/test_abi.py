@@ -133,6 +133,22 @@ def test_argument_errors_before_any_launch():
     assert lib.svdq_gptq_quantize(a, a, -1.0, 128, 128, a, a, a, z) == INV      # negative damping
     assert lib.svdq_gptq_quantize(a, a, 0.01, 128, 100, a, a, a, z) == SHAPE
     assert lib.svdq_gptq_quantize(a, z, 0.01, 128, 128, a, a, a, z) == INV
+    # clipping-ratio search: reduction, accumulation over a bin's steps, arg-min over the candidates
+    for f in (lib.svdq_sq_error, lib.svdq_sq_error_add):
+        assert f(z, 64, a, 64, 4, 64, a, a, z) == INV
+        assert f(a, 64, a, 64, 4, 64, z, a, z) == INV                            # no workspace
+        assert f(a, 64, a, 64, 4, 60, a, a, z) == SHAPE                          # N % 8
+        assert f(a, 32, a, 64, 4, 64, a, a, z) == SHAPE                          # ld_ref < N
+    assert lib.svdq_argmin_rows(z, 4, 5, a, z) == INV and lib.svdq_argmin_rows(a, 4, 0, a, z) == INV
+    assert lib.svdq_argmin_rows(a, 0, 5, a, z) == 0
+    # token counts beyond what the kernels' 32-bit per-lane offsets cover
+    big = (1 << 26) + 1
+    assert q(a, 512, a, 0.9, z, big, 512, 0, a, a, z, z) == SHAPE
+    assert g(a, a, a, z, z, z, big, 512, 512, 0, a, 512, 0, z) == SHAPE
+    assert q6(a, 512, a, 0.9, z, big, 512, 0, a, z, z, z) == SHAPE
+    assert g6(a, a, z, z, z, big, 512, 512, 0, a, 512, 0, z) == SHAPE
+    assert qm(a, 512, a, 0.9, z, big, 512, 0, a, a, z, z) == SHAPE
+    assert gm(a, a, a, z, z, z, big, 512, 512, 0, a, 512, 0, z) == SHAPE
     assert lib.svdq_status_string(-2) == b"unsupported shape"
 
 

@@ -200,6 +200,8 @@ class Layer:
     bias: np.ndarray           # [N] f32
     W: Optional[np.ndarray] = None   # dense [K,N] f32, only kept on request
     fmt: str = "int4"
+    qw_mx: Optional[np.ndarray] = None   # fmt "both": the same residual also as E2M1 codes ...
+    sw_mx: Optional[np.ndarray] = None   # ... and E8M0 bytes [K/32,N] (qw, sw then hold the int4 form)
 
 
 def make_layer(seed: int, K: int, N: int, r: int, x_colmax: np.ndarray,
@@ -223,9 +225,11 @@ def make_layer(seed: int, K: int, N: int, r: int, x_colmax: np.ndarray,
         L1 = np.zeros((K, 0), np.uint16)
         L2 = np.zeros((0, N), np.uint16)
         R = What
-    qw, sw = (mxfp4_weight if fmt == "mxfp4" else rtn_int4_weight)(R.astype(np.float32))
+    R = R.astype(np.float32)
+    qw, sw = (mxfp4_weight if fmt == "mxfp4" else rtn_int4_weight)(R)
+    qw_mx, sw_mx = mxfp4_weight(R) if fmt == "both" else (None, None)
     bias = (_rng(seed, 5).standard_normal(N, dtype=np.float32) * np.float32(0.01)).astype(np.float32)
-    return Layer(K, N, r, lam, inv_lambda, L1, L2, qw, sw, bias, W if keep_dense else None, fmt)
+    return Layer(K, N, r, lam, inv_lambda, L1, L2, qw, sw, bias, W if keep_dense else None, fmt, qw_mx, sw_mx)
 
 
 # --------------------------------------------------------------------------
@@ -253,7 +257,9 @@ def workload(idx: int, M: Optional[int] = None, keep_dense: bool = False, fmt: s
     """Workload `idx` (0-based; the five configurations of the benchmark definition).
 
     `M` overrides the token count (tests use it for row-reduced variants that
-    keep K, N, r and the value distributions).
+    keep K, N, r and the value distributions).  fmt "int4" / "mxfp4" selects the
+    residual's 4-bit format; "both" quantises the same residual both ways (one
+    synthesis serves every execution a benchmark times).
     """
     if idx == 0:
         M = M or 256
