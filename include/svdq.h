@@ -332,6 +332,19 @@ int svdq_sq_error_add(const void* y_ref_bf16, int64_t ld_ref, const void* y_bf16
                       int64_t M, int N, void* workspace, double* acc, void* stream);
 int svdq_argmin_rows(const double* table, int nrows, int ncols, int32_t* idx, void* stream);
 
+/*
+ * svdq_sq_error for callers that cannot allocate device memory or carry a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments without `workspace`, same result bit for
+ * bit.  The 1024 binary64 partial sums live in a static device array of the library (8 KB per GPU, held until the
+ * process ends), whose address is looked up once per device; the call allocates nothing.  The array does not grow
+ * with the input; inputs of more than SVDQ_SQ_ERROR_STATIC_MAX_ELEMENTS = 2^36 elements per tensor are rejected
+ * with SVDQ_ERR_UNSUPPORTED_SHAPE.  All calls on one GPU share the array: calls that overlap on one GPU (two
+ * streams, two threads) race and give wrong sums; calls on one stream are safe, and nothing needs clearing between
+ * them (every partial sum is rewritten by every call).
+ */
+#define SVDQ_SQ_ERROR_STATIC_MAX_ELEMENTS ((int64_t)1 << 36)
+int svdq_sq_error_static(const void* y_ref_bf16, int64_t ld_ref, const void* y_bf16, int64_t ldy,
+                         int64_t M, int N, double* out, void* stream);
 
 /*
  * Test hook: the scalar part of kernel (a)'s chain, eq. 8-9, evaluated by the

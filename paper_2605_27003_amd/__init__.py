@@ -15,6 +15,6 @@ from .binding import (  # noqa: F401
     linear_w4a4_e3m2, linear_w4a4_e3m2_next, debug_group_acc_e3m2,
     FMT_INT4, FMT_INT4_E3M2, FMT_MXFP4, quantize_act_gelu, debug_gelu,
     gptq_hessian, gptq_quantize,
-    sq_error, search_clipping_ratios,
+    sq_error, sq_error_static, search_clipping_ratios,
     W4A4Linear,
 )

@@ -47,6 +47,7 @@ EXPORTS = {
     "svdq_sq_error": (_i32, [_vp, _i64, _vp, _i64, _i64, _i32, _vp, _vp, _vp]),
     "svdq_sq_error_add": (_i32, [_vp, _i64, _vp, _i64, _i64, _i32, _vp, _vp, _vp]),
     "svdq_argmin_rows": (_i32, [_vp, _i32, _i32, _vp, _vp]),
+    "svdq_sq_error_static": (_i32, [_vp, _i64, _vp, _i64, _i64, _i32, _vp, _vp]),
     "svdq_debug_group_acc": (_i32, [_vp, _vp, _i64, _i32, _i32, _i64, _i32, _vp, _vp]),
     "svdq_debug_scale_chain": (_i32, [_vp, _f32, _i64, _vp, _vp, _vp]),
 }
@@ -439,6 +440,18 @@ def sq_error(y_ref, y, workspace=None, out=None):
         out = torch.empty(1, dtype=torch.float64, device=y.device)
     _check(load_library().svdq_sq_error(_ptr(y_ref), y_ref.stride(0) if M > 1 else N, _ptr(y), y.stride(0) if M > 1 else N,
                                         M, N, _ptr(workspace), _ptr(out), _stream()), "svdq_sq_error")
+    return out
+
+
+def sq_error_static(y_ref, y, out=None):
+    """sq_error through the entry point that allocates nothing and takes no workspace (partial sums in the
+    library's static device array)."""
+    M, N = y.shape
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=y.device)
+    _check(load_library().svdq_sq_error_static(_ptr(y_ref), y_ref.stride(0) if M > 1 else N, _ptr(y),
+                                               y.stride(0) if M > 1 else N, M, N, _ptr(out), _stream()),
+           "svdq_sq_error_static")
     return out
 
 

@@ -423,6 +423,15 @@ int svdq_argmin_rows(const double* table, int nrows, int ncols, int32_t* idx, vo
     return hip_status(svdq::launch_argmin_rows(table, nrows, ncols, idx, (hipStream_t)stream));
 }
 
+int svdq_sq_error_static(const void* y_ref_bf16, int64_t ld_ref, const void* y_bf16, int64_t ldy,
+                         int64_t M, int N, double* out, void* stream) {
+    if (!y_ref_bf16 || !y_bf16 || !out || M < 0) return SVDQ_ERR_INVALID_ARG;
+    if (N <= 0 || N % 8 || ld_ref < N || ldy < N || ld_ref % 8 || ldy % 8) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (M > SVDQ_SQ_ERROR_STATIC_MAX_ELEMENTS / N) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (!aligned16(y_ref_bf16) || !aligned16(y_bf16)) return SVDQ_ERR_UNSUPPORTED_SHAPE;
+    if (int a = check_arch()) return a;
+    return hip_status(svdq::launch_sq_error_static(y_ref_bf16, ld_ref, y_bf16, ldy, M, N, out, (hipStream_t)stream));
+}
 
 int svdq_debug_scale_chain(const float* a, float rho, int64_t n, float* s, float* inv, void* stream) {
     if (!a || !s || !inv || n < 0 || n > (int64_t)1 << 31) return SVDQ_ERR_INVALID_ARG;

@@ -67,6 +67,8 @@ hipError_t launch_linear_mx_next(const uint8_t* qx, const uint8_t* sxe, const vo
 constexpr int SQ_ERROR_PARTIALS = 1024;
 hipError_t launch_sq_error(const void* yref, int64_t ldr, const void* y, int64_t ldy, int64_t M, int N,
                            double* workspace, double* out, bool add, hipStream_t stream);
+hipError_t launch_sq_error_static(const void* yref, int64_t ldr, const void* y, int64_t ldy, int64_t M, int N,
+                                  double* out, hipStream_t stream);
 hipError_t launch_argmin_rows(const double* table, int nrows, int ncols, int32_t* idx, hipStream_t stream);
 
 // svdq_gptq.hip (offline calibration)

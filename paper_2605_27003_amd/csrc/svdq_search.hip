@@ -8,6 +8,8 @@
 //
 // Also here: the expectation over a bin's calibration steps (the same reduction ADDED to a device accumulator) and
 // the arg-min over the candidates, so that a C caller can run the whole search without host arithmetic.
+#include <mutex>
+
 #include "svdq_dev.h"
 #include "svdq_kernels.h"
 
@@ -15,6 +17,10 @@ namespace svdq {
 
 namespace {
 
+// Partial sums of svdq_sq_error_static: one file-scope array per GPU (each device that loads the library holds its
+// own copy until the process ends), for callers that may not allocate.  In host code this name is only a handle:
+// the device address comes from hipGetSymbolAddress (static_partials below) and is what the kernels receive.
+static __device__ __align__(256) double scratch[SQ_ERROR_PARTIALS];
 
 __global__ __launch_bounds__(256)
 void sq_error_partial_kernel(const uint16_t* __restrict__ yref, int64_t ldr, const uint16_t* __restrict__ y, int64_t ldy,
@@ -68,6 +74,26 @@ __global__ void argmin_rows_kernel(const double* __restrict__ table, int nrows, 
     idx[row] = best;
 }
 
+// Device address of `scratch` on the current device, looked up once per device.
+hipError_t static_partials(double** out) {
+    static std::mutex mu;
+    static double* ptr[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        double* p = nullptr;
+        e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return hipSuccess;
+}
+
 }  // namespace
 
 hipError_t launch_sq_error(const void* yref, int64_t ldr, const void* y, int64_t ldy, int64_t M, int N,
@@ -79,6 +105,16 @@ hipError_t launch_sq_error(const void* yref, int64_t ldr, const void* y, int64_t
     else
         hipLaunchKernelGGL(sq_error_final_kernel<false>, dim3(1), dim3(64), 0, stream, workspace, SQ_ERROR_PARTIALS, out);
     return hipGetLastError();
+}
+
+// The same two kernels with the partial sums in this GPU's `scratch`: no allocation, no workspace argument.  Every
+// block writes its partial sum on every call, so nothing has to be cleared between calls.
+hipError_t launch_sq_error_static(const void* yref, int64_t ldr, const void* y, int64_t ldy, int64_t M, int N,
+                                  double* out, hipStream_t stream) {
+    double* partials = nullptr;
+    const hipError_t e = static_partials(&partials);
+    if (e != hipSuccess) return e;
+    return launch_sq_error(yref, ldr, y, ldy, M, N, partials, out, false, stream);
 }
 
 hipError_t launch_argmin_rows(const double* table, int nrows, int ncols, int32_t* idx, hipStream_t stream) {

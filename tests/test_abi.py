@@ -141,6 +141,11 @@ def test_argument_errors_before_any_launch():
         assert f(a, 32, a, 64, 4, 64, a, a, z) == SHAPE                          # ld_ref < N
     assert lib.svdq_argmin_rows(z, 4, 5, a, z) == INV and lib.svdq_argmin_rows(a, 4, 0, a, z) == INV
     assert lib.svdq_argmin_rows(a, 0, 5, a, z) == 0
+    # the same reduction without a workspace (static device scratch): same checks plus its size limit
+    fs = lib.svdq_sq_error_static
+    assert fs(z, 64, a, 64, 4, 64, a, z) == INV and fs(a, 64, a, 64, 4, 64, z, z) == INV
+    assert fs(a, 64, a, 64, 4, 60, a, z) == SHAPE and fs(a, 64, a, 32, 4, 64, a, z) == SHAPE
+    assert fs(a, 1 << 20, a, 1 << 20, (1 << 16) + 1, 1 << 20, a, z) == SHAPE     # more than 2^36 elements
     # token counts beyond what the kernels' 32-bit per-lane offsets cover
     big = (1 << 26) + 1
     assert q(a, 512, a, 0.9, z, big, 512, 0, a, a, z, z) == SHAPE
