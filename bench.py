@@ -8,7 +8,7 @@ its fused low-rank/bias/bf16 epilogue, walking the 40-step schedule of the two e
 clipping ratio looked up per timestep bin).  The three single-layer configurations at M = 32760 (attention output
 projection, FFN up, FFN down) are timed in the same run and reported as sub-records under "configs".
 
-Every workload is timed in three executions of the layer:
+Every workload is timed in these executions of the layer:
   "e3m2"   int4 codes held as E3M2 fields, exact integer group sums on the FP6 matrix cores (the fast execution);
            the weights stay RESIDENT in the canonical 4-bit form and are expanded into a shared staging buffer
            inside the timed step ("e3m2_prepacked" = the same with the expanded weights resident instead)
@@ -59,6 +59,17 @@ def measured_traffic(workload_name, kernel):
         return None
     m = re.search(rf"^traffic_bytes_per_(?:launch|step)\s+{kernel}\s+(\d+)", text, re.M)
     return int(m.group(1)) if m else None
+
+
+def measured_clock(workload_name, kernel):
+    """Clock the chip sustained under one kernel (SQ_BUSY_CYCLES / duration of the same dispatches, GHz), from the
+    committed rocprofv3 counter summary of this workload, or None.  The matrix-core peaks are quoted at 2.4 GHz."""
+    try:
+        text = open(os.path.join(ROOT, "profiles", f"{workload_name}_sq_counters.txt")).read()
+    except OSError:
+        return None
+    m = re.search(rf"^achieved_clock_ghz\s+{kernel}\s+([0-9.]+)", text, re.M)
+    return float(m.group(1)) if m else None
 
 
 def cpu_baseline(w, rows, seed=7):
@@ -167,6 +178,9 @@ def main():
         M = w.M
         single = len(w.layers) == 1
         xdev = {k: dev(v) for k, v in w.x.items()}
+        # a plain copy of known size (reads and writes every byte of the first input once): the reference against
+        # which the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the kernels are scaled (profiles/*_hbm_traffic.txt)
+        next(iter(xdev.values())).roll(1, dims=0)
         if single:                                     # rotate input sets: the 256 MB memory-side cache must not hold them
             (xname, x0), = xdev.items()
             xsets = [x0] + [x0.roll(17 * (i + 1), dims=0).contiguous() for i in range(args.xsets - 1)]
@@ -252,11 +266,13 @@ def main():
                               "quantize_frac": M * (2 * K + K // 2 + sb(K) + 4 * r) / (mq * 1e-3) / 1e9 / HBM_PEAK_GBS})
         rg = {"kernel": f"{ENTRY[fmt][0]} ({gk}){launches}", "bound": "mfma", "achieved": g, "peak": peak, "unit": unit,
               "frac": g / peak, "traffic": measured_traffic(w.name, gk), "algorithmic_ops": ops,
+              "clock_ghz_under_this_kernel": measured_clock(w.name, gk),
               "avg_ms": float(tg.mean()), "min_ms": float(tg.min())}
         if fmt == "e3m2":
             rg["frac_of_int8_peak"] = g / INT8_MFMA_PEAK_TOPS      # the same integer work priced at the int8 rate
         rq = {"kernel": f"{ENTRY[fmt][1]} ({qk.replace('_e3m2', '')}){launches}", "bound": "hbm", "achieved": q,
               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": q / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, qk),
+              "clock_ghz_under_this_kernel": measured_clock(w.name, qk),
               "algorithmic_bytes": bytes_q, "avg_ms": float(tq.mean()), "min_ms": float(tq.min())}
         if nl > 1:
             rg["traffic_unit"] = rq["traffic_unit"] = f"bytes per step ({nl} launches)"

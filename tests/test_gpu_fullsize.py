@@ -97,6 +97,19 @@ def check_layer(svdq, oracle, name, x_bits, x_dev, L, DL, rho, n_sample, whole, 
     val = np.where((f >> 2) & 7, (4 + (f & 3)) * 2.0 ** (((f >> 2) & 7) - 5.0), (f & 3) / 16.0) * np.where(f >> 5, -1.0, 1.0)
     assert np.array_equal(val.transpose(1, 0, 2, 3).reshape(len(S), L.K), synth.unpack_int4(oq)), f"{name}: E3M2 fields (row sample)"
     del rows, bits, f, val
+    # the scale-piece plane: per (group, token) the pair {p, p}, p = hi | lo << 16 with hi = bf16(s), lo = bf16(s - hi)
+    # of the oracle's binary32 scale s (round to nearest even, torch's cast): sampled rows against the oracle, and
+    # the whole plane against the same split of the scales that were compared with the oracle above
+    def pieces(s32):                                           # torch tensor of binary32 scales -> uint32 p (as int64)
+        hi = s32.to(torch.bfloat16)
+        lo = (s32 - hi.float()).to(torch.bfloat16)
+        return (hi.view(torch.int16).to(torch.int64) & 0xFFFF) | ((lo.view(torch.int16).to(torch.int64) & 0xFFFF) << 16)
+    plane = blk[:, Mp * 48:].reshape(ng, Mp, 8)[:, :M].contiguous().view(torch.int32).to(torch.int64) & 0xFFFFFFFF
+    assert torch.equal(plane[..., 0], plane[..., 1]), f"{name}: scale pieces are stored twice"
+    want_s = pieces(torch.from_numpy(os_).t().contiguous())                     # [ng, |S|] from the ORACLE's scales
+    assert torch.equal(plane[:, St, 0].cpu(), want_s), f"{name}: E3M2 scale pieces (row sample, oracle scales)"
+    assert torch.equal(plane[..., 0], pieces(sx)), f"{name}: E3M2 scale pieces (whole plane)"
+    del plane, want_s
     if whole:
         for m0 in (0, M - acc_rows):
             acc = svdq.debug_group_acc_e3m2(act, DL.wp6, L.N, m0, acc_rows).cpu().numpy()
@@ -170,6 +183,14 @@ def test_block_720p_schedule(svdq, oracle, block720p, expert):
             check_layer(svdq, oracle, f"{w.name}/{expert}/step{step}/{lin}", xb, xd, DL.L, DL, rho,
                         n_sample=256, whole=int(si == 0 and lin in ("q", "ffn_down")), seed=step)
             del xd
+    # one step per expert on FRESH activations (new values of the same distribution, seeded by the step) for the
+    # down-projection, the layer whose post-GELU input the paper singles out: 2048 sampled rows
+    step = steps[1]
+    rho = svdq.alpha_lookup(table, step, step0, nsteps)
+    xb, _ = synth.block_input("x_down", w.M, step=step)
+    progress(f"{w.name}/{expert}: fresh x_down for step {step} generated")
+    check_layer(svdq, oracle, f"{w.name}/{expert}/step{step}/ffn_down/fresh-x", xb, dev(xb), layers["ffn_down"].L,
+                layers["ffn_down"], rho, n_sample=2048, whole=0, seed=1000 + step)
 
 
 @pytest.mark.parametrize("fmt", ["int4", "mxfp4"])

@@ -47,13 +47,14 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 def make_x(seed: int, M: int, K: int, kind: str = "normal",
            outlier_frac: float = 0.0, outlier_count: int = 0, outlier_scale: float = 1.0,
            heavy_count: int = 0, heavy_scale: float = 1.0, sigma: float = 1.0,
-           chunk_rows: int = 4096):
+           chunk_rows: int = 4096, value_seed: Optional[int] = None):
     """Activation matrix as bf16 bits [M,K] plus the per-channel max |x| (float32).
 
     kind "normal": N(0, sigma^2); kind "gelu": GELU(z), z ~ N(0, sigma^2).
     `outlier_count` (or round(outlier_frac*K)) channels are scaled by
     outlier_scale, a further `heavy_count` channels by heavy_scale; channels are
-    drawn without replacement from the same generator.
+    drawn without replacement from the same generator.  `value_seed` (default:
+    `seed`) keys the value streams only: the outlier channels stay those of `seed`.
     """
     g_ch = _rng(seed, 1)
     n_out = outlier_count if outlier_count else int(round(outlier_frac * K))
@@ -68,7 +69,7 @@ def make_x(seed: int, M: int, K: int, kind: str = "normal",
         # every chunk has its own counter-based stream, so the result does not depend on the thread count
         m0 = bounds[ci]
         m1 = min(M, m0 + chunk_rows)
-        g = np.random.Generator(np.random.Philox(key=[int(seed), 2 + (ci << 8)]))
+        g = np.random.Generator(np.random.Philox(key=[int(seed if value_seed is None else value_seed), 2 + (ci << 8)]))
         z = g.standard_normal((m1 - m0, K), dtype=np.float32)
         if sigma != 1.0:
             z *= np.float32(sigma)
@@ -235,6 +236,25 @@ def make_layer(seed: int, K: int, N: int, r: int, x_colmax: np.ndarray,
 # --------------------------------------------------------------------------
 # the five workloads
 # --------------------------------------------------------------------------
+# inputs of the DiT block workload: name -> (seed, K, make_x arguments)
+BLOCK_INPUTS = {
+    "x_qkv": (50, 5120, dict(outlier_frac=0.005, outlier_scale=50.0)),
+    "x_o": (51, 5120, dict(outlier_frac=0.005, outlier_scale=50.0)),
+    "x_up": (52, 5120, dict(outlier_frac=0.005, outlier_scale=50.0, heavy_count=8, heavy_scale=100.0)),
+    "x_down": (53, 13824, dict(kind="gelu", sigma=1.5)),
+}
+
+
+def block_input(name: str, M: int, step: Optional[int] = None):
+    """Input `name` of the DiT block workload: (bf16 bits [M,K], per-channel max).  step=None is the base input the
+    layers were calibrated on; a denoising step number draws fresh values of the same distribution (seed + 1000 *
+    (step + 1)) with the SAME outlier channels (the channel pattern belongs to the layer, not to the step)."""
+    seed, K, kw = BLOCK_INPUTS[name]
+    if step is None:
+        return make_x(seed, M, K, **kw)
+    return make_x(seed, M, K, value_seed=seed + 1000 * (step + 1), **kw)
+
+
 @dataclass
 class Workload:
     name: str
@@ -284,11 +304,8 @@ def workload(idx: int, M: Optional[int] = None, keep_dense: bool = False, fmt: s
     if idx == 4:
         M = M or 75600
         xs, cms = {}, {}
-        xs["x_qkv"], cms["x_qkv"] = make_x(50, M, 5120, outlier_frac=0.005, outlier_scale=50.0)
-        xs["x_o"], cms["x_o"] = make_x(51, M, 5120, outlier_frac=0.005, outlier_scale=50.0)
-        xs["x_up"], cms["x_up"] = make_x(52, M, 5120, outlier_frac=0.005, outlier_scale=50.0,
-                                         heavy_count=8, heavy_scale=100.0)
-        xs["x_down"], cms["x_down"] = make_x(53, M, 13824, kind="gelu", sigma=1.5)
+        for name in BLOCK_INPUTS:
+            xs[name], cms[name] = block_input(name, M)
         shapes = {"q": ("x_qkv", 5120, 5120), "k": ("x_qkv", 5120, 5120), "v": ("x_qkv", 5120, 5120),
                   "o": ("x_o", 5120, 5120), "ffn_up": ("x_up", 5120, 13824), "ffn_down": ("x_down", 13824, 5120)}
         layers, tables, jobs = {}, {}, []
