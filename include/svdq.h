@@ -259,8 +259,9 @@ int svdq_debug_gelu(const void* x_bf16, int64_t n, void* out_bf16, void* stream)
  *   svdq_gptq_quantize: R [K, N] binary32 residual (row k = input channel), H as above (not modified),
  *                       workspace of svdq_gptq_workspace_bytes(N, K) bytes (16-byte aligned, device);
  *                       out qw [N, K/2] packed codes and sw [K/64, N] binary32 scales: the canonical weight form
- *                       that svdq_pack_weight and svdq_pack_weight_e3m2 take.  K % 64 == 0.  Enqueues about 5 K
- *                       small kernels on `stream`.
+ *                       that svdq_pack_weight and svdq_pack_weight_e3m2 take.  K % 64 == 0.  The pivots are taken
+ *                       in panels of 64 (same rounded operations per element in the same order, so the result
+ *                       does not depend on it); enqueues about 5 * K small kernels on `stream`.
  */
 size_t svdq_gptq_workspace_bytes(int N, int K);
 int svdq_gptq_hessian(const void* x_bf16, int64_t ldx, const float* inv_lambda, int64_t M, int K, double* H, void* stream);

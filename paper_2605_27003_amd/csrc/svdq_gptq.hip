@@ -8,7 +8,8 @@
 // binary64 with one explicitly rounded operation per arithmetic step and no reductions other than max and one
 // sequential sum, so that a CPU reference repeats every bit.  The published implementation factors H^-1 once
 // (Cholesky) and reads the same numbers off the factor; this form trades that for elementwise kernels:
-// K^3 / 3 updates of H^-1 and K^2 N / 2 updates of the weights, about a second for a 5120 x 5120 layer.
+// K^3 updates for the inverse, K^3 / 3 of H^-1 and K^2 N / 2 of the weights during the visit, taken in panels of 64
+// pivots (below) so that the matrices cross HBM once per panel.
 #include "svdq_dev.h"
 #include "svdq_kernels.h"
 
@@ -81,31 +82,102 @@ __global__ void prepare_kernel(const float* __restrict__ R, const double* __rest
     }
 }
 
-// ---- in-place Gauss-Jordan inverse without pivoting, step p
-__global__ void gj_pivot_kernel(const double* __restrict__ A, int K, int p, double* __restrict__ col, double* __restrict__ row) {
+// ---- Panel-blocked form of both eliminations.  Every element of H^-1 (and of W) must receive, in the order of the
+// pivots, one rounded product and one rounded subtraction per pivot: that sequence per element is the definition, and
+// it does not say WHEN an element is touched.  Pivots are taken in panels of PB = 64.  Inside a panel only the panel's
+// own rows and columns (2 x 64 x K elements) are brought up to date after every pivot, by small kernels, and each
+// pivot's column (as it stood when the pivot was taken) and scaled row are saved; everything else receives its 64
+// updates in one pass at the end of the panel from the saved columns and rows, in pivot order, with the same two
+// rounded operations per update.  Bit-identical to the pivot-by-pivot form; the K x K matrix crosses HBM once per
+// panel instead of once per pivot.
+constexpr int PB = 64;
+
+// X[a][b] <- (..((X[a][b] - L[a][0] R[0][b]) - L[a][1] R[1][b]).. - L[a][PB-1] R[PB-1][b]) for a in [a0, a1),
+// b in [b0, b1), skipping the 64-aligned index block [skip, skip + PB) in both directions (skip < 0: none).
+// L is [rows][PB], R is [PB][ldr].  a0, a1, b0 multiples of 64.  One 64 x 64 tile per block, 4 x 4 elements per thread.
+__global__ __launch_bounds__(256)
+void seq_rank_update_kernel(double* __restrict__ X, size_t ldx, int a0, int a1, int b0, int b1, int skip,
+                            const double* __restrict__ L, const double* __restrict__ R, size_t ldr) {
+    __shared__ double Lt[PB][64];       // Lt[q][row]
+    __shared__ double Rs[PB][64];       // Rs[q][col]
+    const int ta = a0 + blockIdx.y * 64, tb = b0 + blockIdx.x * 64;
+    if (ta == skip || tb == skip) return;
+    for (int e = threadIdx.x; e < 64 * PB; e += 256) {
+        const int rr = e / PB, q = e - rr * PB;
+        Lt[q][rr] = (ta + rr < a1) ? L[(size_t)(ta + rr) * PB + q] : 0.0;
+        const int qq = e / 64, c = e - qq * 64;
+        Rs[qq][c] = (tb + c < b1) ? R[(size_t)qq * ldr + tb + c] : 0.0;
+    }
+    __syncthreads();
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    double v[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int a = ta + ty * 4 + i, c = tb + tx * 4 + j;
+            v[i][j] = (a < a1 && c < b1) ? X[(size_t)a * ldx + c] : 0.0;
+        }
+    for (int q = 0; q < PB; ++q) {
+        double l[4], r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) l[i] = Lt[q][ty * 4 + i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[j] = Rs[q][tx * 4 + j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[i][j] = __dsub_rn(v[i][j], __dmul_rn(l[i], r[j]));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int a = ta + ty * 4 + i, c = tb + tx * 4 + j;
+            if (a < a1 && c < b1) X[(size_t)a * ldx + c] = v[i][j];
+        }
+}
+
+// ---- in-place Gauss-Jordan inverse without pivoting.  Step p: d = A[p][p], col = A[:, p], row = A[p, :] / d;
+// A[a][j] -= col[a] row[j] elsewhere, A[p][j] = row[j], A[a][p] = -col[a] / d, A[p][p] = 1 / d.
+// gj_pivot: save col and row of pivot p (panel starting at p0) as they stand.
+__global__ void gj_pivot_kernel(const double* __restrict__ A, int K, int p, int p0, double* __restrict__ C, double* __restrict__ Rw) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= K) return;
     const double d = A[(size_t)p * K + p];
-    col[i] = A[(size_t)i * K + p];
-    row[i] = __ddiv_rn(A[(size_t)p * K + i], d);
+    C[(size_t)i * PB + (p - p0)] = A[(size_t)i * K + p];
+    Rw[(size_t)(p - p0) * K + i] = __ddiv_rn(A[(size_t)p * K + i], d);
 }
-__global__ void gj_update_kernel(double* __restrict__ A, int K, int p, const double* __restrict__ col, const double* __restrict__ row) {
+// gj_panel: apply step p to the panel's columns (all rows) and the panel's rows (all other columns)
+__global__ void gj_panel_kernel(double* __restrict__ A, int K, int p, int p0, const double* __restrict__ C, const double* __restrict__ Rw) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    const double d = col[p];
-    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < (size_t)K * K; e += stride) {
-        const int a = (int)(e / K), j = (int)(e - (size_t)a * K);
+    const int q = p - p0;
+    const double d = C[(size_t)p * PB + q];
+    const size_t n1 = (size_t)K * PB, total = n1 + (size_t)PB * (K - PB);
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
+        int a, j;
+        if (e < n1) {                                   // the panel's columns
+            a = (int)(e / PB);
+            j = p0 + (int)(e - (size_t)a * PB);
+        } else {                                        // the panel's rows, columns outside the panel
+            const size_t f = e - n1;
+            a = p0 + (int)(f / (K - PB));
+            j = (int)(f - (size_t)(a - p0) * (K - PB));
+            if (j >= p0) j += PB;
+        }
+        const size_t at = (size_t)a * K + j;
         double v;
-        if (a == p) v = (j == p) ? __ddiv_rn(1.0, d) : row[j];
-        else if (j == p) v = __ddiv_rn(-col[a], d);
-        else v = __dsub_rn(A[e], __dmul_rn(col[a], row[j]));
-        A[e] = v;
+        if (a == p) v = (j == p) ? __ddiv_rn(1.0, d) : Rw[(size_t)q * K + j];
+        else if (j == p) v = __ddiv_rn(-C[(size_t)a * PB + q], d);
+        else v = __dsub_rn(A[at], __dmul_rn(C[(size_t)a * PB + q], Rw[(size_t)q * K + j]));
+        A[at] = v;
     }
 }
 
-// ---- column i: scale at a group start, code, error
-__global__ void column_kernel(const double* __restrict__ W, const double* __restrict__ Hinv, int N, int K, int i,
+// ---- column i: scale at a group start, code, error (kept in Err[i - i0][:] for the deferred spreading)
+__global__ void column_kernel(const double* __restrict__ W, const double* __restrict__ Hinv, int N, int K, int i, int i0,
                               float* __restrict__ scur, float* __restrict__ sw, int8_t* __restrict__ codes,
-                              double* __restrict__ err) {
+                              double* __restrict__ Err) {
     const int n = blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
     float s;
@@ -122,24 +194,45 @@ __global__ void column_kernel(const double* __restrict__ W, const double* __rest
     float q = 0.0f;
     if (s > 0.0f) q = fminf(fmaxf(rintf(__fdiv_rn((float)w, s)), -8.0f), 7.0f);
     codes[(size_t)i * N + n] = (int8_t)q;
-    err[n] = __ddiv_rn(__dsub_rn(w, __dmul_rn((double)q, (double)s)), Hinv[(size_t)i * K + i]);
+    Err[(size_t)(i - i0) * N + n] = __ddiv_rn(__dsub_rn(w, __dmul_rn((double)q, (double)s)), Hinv[(size_t)i * K + i]);
 }
-// ---- spread the error over the weights not yet visited
-__global__ void spread_kernel(double* __restrict__ W, const double* __restrict__ Hinv, const double* __restrict__ err,
-                              int N, int K, int i) {
-    const size_t total = (size_t)(K - 1 - i) * N, stride = (size_t)gridDim.x * blockDim.x;
+// ---- spread the error of column i over the panel's not yet visited weights (rows i + 1 .. i0 + PB - 1)
+__global__ void spread_panel_kernel(double* __restrict__ W, const double* __restrict__ Hinv, const double* __restrict__ Err,
+                                    int N, int K, int i, int i0) {
+    const size_t total = (size_t)(i0 + PB - 1 - i) * N, stride = (size_t)gridDim.x * blockDim.x;
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
         const int j = i + 1 + (int)(e / N), n = (int)(e % N);
-        W[(size_t)j * N + n] = __dsub_rn(W[(size_t)j * N + n], __dmul_rn(Hinv[(size_t)i * K + j], err[n]));
+        W[(size_t)j * N + n] = __dsub_rn(W[(size_t)j * N + n], __dmul_rn(Hinv[(size_t)i * K + j], Err[(size_t)(i - i0) * N + n]));
     }
 }
-// ---- eliminate index i from the inverse Hessian
-__global__ void eliminate_kernel(double* __restrict__ Hinv, int K, int i) {
-    const int rem = K - 1 - i;
-    const size_t total = (size_t)rem * rem, stride = (size_t)gridDim.x * blockDim.x;
+// ---- eliminate index i from the inverse Hessian inside the panel: Hinv[a][b] -= Hinv[a][i] (Hinv[i][b] / d) for
+// a, b > i with a or b in the panel; row i, scaled row i and column i are saved for the deferred updates
+// (HrowT[j][q] = Hinv[i][j], T[q][b] = Hinv[i][b] / d, Hc[a][q] = Hinv[a][i]); row and column i are not written.
+__global__ void eliminate_panel_kernel(double* __restrict__ Hinv, int K, int i, int i0,
+                                       double* __restrict__ HrowT, double* __restrict__ T, double* __restrict__ Hc) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x, t0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int q = i - i0, i1 = i0 + PB;
     const double d = Hinv[(size_t)i * K + i];
-    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
-        const int a = i + 1 + (int)(e / rem), b = i + 1 + (int)(e % rem);
+    for (size_t e = t0; e < (size_t)K; e += stride) {
+        const int j = (int)e;
+        const double hij = Hinv[(size_t)i * K + j];
+        HrowT[(size_t)j * PB + q] = hij;
+        T[(size_t)q * K + j] = __ddiv_rn(hij, d);
+        Hc[(size_t)j * PB + q] = Hinv[(size_t)j * K + i];
+    }
+    const int rp = i1 - 1 - i;                          // panel rows / columns still alive after i
+    const int rem = K - 1 - i;                          // indices > i
+    const size_t n1 = (size_t)rp * rem, total = n1 + (size_t)(K - i1) * rp;
+    for (size_t e = t0; e < total; e += stride) {
+        int a, b;
+        if (e < n1) {                                   // rows of the panel, every column > i
+            a = i + 1 + (int)(e / rem);
+            b = i + 1 + (int)(e % rem);
+        } else {                                        // rows below the panel, columns of the panel
+            const size_t f = e - n1;
+            a = i1 + (int)(f / rp);
+            b = i + 1 + (int)(f % rp);
+        }
         const double t = __ddiv_rn(Hinv[(size_t)i * K + b], d);
         Hinv[(size_t)a * K + b] = __dsub_rn(Hinv[(size_t)a * K + b], __dmul_rn(Hinv[(size_t)a * K + i], t));
     }
@@ -160,8 +253,8 @@ inline unsigned blocks_for(size_t n) { size_t b = (n + 255) / 256; return (unsig
 }  // namespace
 
 size_t gptq_workspace_bytes(int N, int K) {
-    return up256((size_t)K * K * 8) + up256((size_t)K * N * 8) + up256((size_t)N * 8) + up256((size_t)N * 4) +
-           2 * up256((size_t)K * 8) + up256((size_t)K * N);
+    return up256((size_t)K * K * 8) + up256((size_t)K * N * 8) + up256((size_t)N * 4) + up256((size_t)K * N) +
+           4 * up256((size_t)K * PB * 8) + up256((size_t)PB * N * 8);
 }
 
 hipError_t launch_gptq_hessian(const void* x, int64_t ldx, const float* inv_lambda, int64_t M, int K, double* H,
@@ -176,21 +269,38 @@ hipError_t launch_gptq_quantize(const float* R, const double* H, double damp, in
     uint8_t* p = (uint8_t*)workspace;
     double* A = (double*)p;        p += up256((size_t)K * K * 8);
     double* W = (double*)p;        p += up256((size_t)K * N * 8);
-    double* err = (double*)p;      p += up256((size_t)N * 8);
     float* scur = (float*)p;       p += up256((size_t)N * 4);
-    double* col = (double*)p;      p += up256((size_t)K * 8);
-    double* row = (double*)p;      p += up256((size_t)K * 8);
-    int8_t* codes = (int8_t*)p;
+    int8_t* codes = (int8_t*)p;    p += up256((size_t)K * N);
+    double* Lc = (double*)p;       p += up256((size_t)K * PB * 8);     // saved pivot columns      [K][PB]
+    double* Rr = (double*)p;       p += up256((size_t)K * PB * 8);     // saved scaled pivot rows  [PB][K]
+    double* HrowT = (double*)p;    p += up256((size_t)K * PB * 8);     // saved rows of H^-1       [K][PB]
+    double* Hc = (double*)p;       p += up256((size_t)K * PB * 8);     // saved columns of H^-1    [K][PB]
+    double* Err = (double*)p;                                          // errors of the panel      [PB][N]
+    const dim3 tilesKK((unsigned)(K / 64), (unsigned)(K / 64));
     hipLaunchKernelGGL(prepare_kernel, dim3(1024), dim3(256), 0, stream, R, H, damp, N, K, A, W);
-    for (int q = 0; q < K; ++q) {
-        hipLaunchKernelGGL(gj_pivot_kernel, dim3((K + 255) / 256), dim3(256), 0, stream, A, K, q, col, row);
-        hipLaunchKernelGGL(gj_update_kernel, dim3(blocks_for((size_t)K * K)), dim3(256), 0, stream, A, K, q, col, row);
+    for (int p0 = 0; p0 < K; p0 += PB) {               // Gauss-Jordan, one panel of pivots at a time
+        for (int q = p0; q < p0 + PB; ++q) {
+            hipLaunchKernelGGL(gj_pivot_kernel, dim3((K + 255) / 256), dim3(256), 0, stream, A, K, q, p0, Lc, Rr);
+            hipLaunchKernelGGL(gj_panel_kernel, dim3(blocks_for((size_t)K * PB * 2)), dim3(256), 0, stream, A, K, q, p0, Lc, Rr);
+        }
+        if (K > PB)
+            hipLaunchKernelGGL(seq_rank_update_kernel, tilesKK, dim3(256), 0, stream, A, (size_t)K, 0, K, 0, K, p0, Lc, Rr, (size_t)K);
     }
-    for (int i = 0; i < K; ++i) {
-        hipLaunchKernelGGL(column_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, W, A, N, K, i, scur, sw, codes, err);
-        if (i + 1 < K) {
-            hipLaunchKernelGGL(spread_kernel, dim3(blocks_for((size_t)(K - 1 - i) * N)), dim3(256), 0, stream, W, A, err, N, K, i);
-            hipLaunchKernelGGL(eliminate_kernel, dim3(blocks_for((size_t)(K - 1 - i) * (K - 1 - i))), dim3(256), 0, stream, A, K, i);
+    for (int i0 = 0; i0 < K; i0 += PB) {               // the weights, one panel (= one 64-group) at a time
+        const int i1 = i0 + PB;
+        for (int i = i0; i < i1; ++i) {
+            hipLaunchKernelGGL(column_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, W, A, N, K, i, i0, scur, sw, codes, Err);
+            if (i + 1 < i1)
+                hipLaunchKernelGGL(spread_panel_kernel, dim3(blocks_for((size_t)(i1 - 1 - i) * N)), dim3(256), 0, stream, W, A, Err, N, K, i, i0);
+            if (i1 < K || i + 1 < i1)
+                hipLaunchKernelGGL(eliminate_panel_kernel, dim3(blocks_for((size_t)K * PB)), dim3(256), 0, stream, A, K, i, i0, HrowT, Rr, Hc);
+        }
+        if (i1 < K) {                                   // the deferred updates of everything behind the panel
+            const int rest = K - i1;
+            hipLaunchKernelGGL(seq_rank_update_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)(rest / 64)), dim3(256), 0, stream,
+                               W, (size_t)N, i1, K, 0, N, -1, HrowT, Err, (size_t)N);
+            hipLaunchKernelGGL(seq_rank_update_kernel, dim3((unsigned)(rest / 64), (unsigned)(rest / 64)), dim3(256), 0, stream,
+                               A, (size_t)K, i1, K, i1, K, -1, Hc, Rr, (size_t)K);
         }
     }
     hipLaunchKernelGGL(pack_codes_kernel, dim3(blocks_for((size_t)N * (K / 2))), dim3(256), 0, stream, codes, N, K, qw);
