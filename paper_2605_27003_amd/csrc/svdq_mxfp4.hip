@@ -17,6 +17,8 @@
 // shared exponent is read off the binary32 exponent of rho * absmax (eq. 8), and
 // v_cvt_scalef32_pk_fp4_f32 rounds two values at a time to E2M1 (nearest, ties to the even code,
 // saturating; checked against the definition on 2e5 random and all boundary inputs).
+#include <atomic>
+
 #include "svdq_act.h"
 #include "svdq_dev.h"
 #include "svdq_epilogue.h"
@@ -921,15 +923,15 @@ hipError_t launch_quantize_mx(const void* x, int64_t ldx, const float* inv_lambd
 
 // compute units of the current device (256 on MI355X; fewer in a partitioned mode), cached per device
 static int cu_count() {
-    static int cached[64] = {0};
+    static std::atomic<int> cached[64];              // 0 = not asked yet; any thread may call the library
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);     // racing threads store the same value
     }
-    return cached[dev];
+    return n;
 }
 
 // the tile-walking kernel runs one block per CU (a multiple of 8 blocks, so that a block stays on one XCD's share of
