@@ -215,6 +215,13 @@ int svdq_linear_w4a4_e3m2(const uint8_t* act, const void* w_packed,
  *   next_h    out [M, next_r] binary32.  Zeroed by the call, then every tile adds its 64-channel share
  *             with floating-point atomic adds: the summation order, hence the last bits, vary from
  *             run to run (the separate quantise kernel sums in a fixed order).
+ * "Bit for bit" is against THIS library's two-call sequence.  Against an independent implementation of
+ * the chain (first layer, bf16 rounding, GELU, second layer's quantiser) the operands agree exactly
+ * wherever the two implementations' bf16 outputs of the first layer agree: y itself is only fixed up to
+ * the layer's tolerance, and one bf16 step in any of a token's 64 activations of a group can move that
+ * group's scale and codes (on the synthetic feed-forward block 81 % of the (token, group) pairs agree in
+ * all 64 activations, 90 % of the 32-blocks for the MXFP4 variant; elsewhere the scale stays within
+ * 2^-6 relative and the dequantised values within 1.15 scale steps).
  * Shapes, alignment and error behaviour as svdq_linear_w4a4_e3m2 and svdq_quantize_act_e3m2. */
 int svdq_linear_w4a4_e3m2_next(const uint8_t* act, const void* w_packed,
                                const float* h, const void* L2_bf16, const float* bias,

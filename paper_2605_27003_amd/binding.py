@@ -488,23 +488,46 @@ def debug_scale_chain(a, rho):
     return s, inv
 
 
+_staging = {}        # device -> uint8 tensor shared by every W4A4Linear that keeps its weights in the canonical form
+
+
+def _staging_buffer(nbytes, device):
+    buf = _staging.get(device)
+    if buf is None or buf.numel() < nbytes:
+        buf = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        _staging[device] = buf
+    return buf
+
+
 class W4A4Linear:
-    """One quantised linear resident in HBM: packed weights and low-rank factors, reusable output buffers.
+    """One quantised linear resident in HBM: weights and low-rank factors, reusable output buffers.
 
     container "e3m2" (default) runs the int4 layer on the FP6 matrix cores, "nibble" the same layer on 4-bit storage
-    and the int8 matrix cores, "mxfp4" the MXFP4 format (qw then holds E2M1 codes and sw [K/32, N] E8M0 bytes)."""
+    and the int8 matrix cores, "mxfp4" the MXFP4 format (qw then holds E2M1 codes and sw [K/32, N] E8M0 bytes).
+    resident "w4" (default, container "e3m2" only) keeps the canonical 4-bit weights (qw, sw) and expands them into a
+    staging buffer shared by all such layers of the device right before every GEMM (calls on one stream only);
+    "packed" keeps the container's own packed form (7 - 8 bits per weight for the int4 containers)."""
 
-    def __init__(self, inv_lambda, L1_bf16, L2_bf16, qw, sw, bias, container="e3m2"):
-        assert container in ("e3m2", "nibble", "mxfp4")
+    def __init__(self, inv_lambda, L1_bf16, L2_bf16, qw, sw, bias, container="e3m2", resident="w4"):
+        assert container in ("e3m2", "nibble", "mxfp4") and resident in ("w4", "packed")
         self.container = container
         self.N, self.K = qw.shape[0], qw.shape[1] * 2
         self.r = 0 if L1_bf16 is None else L1_bf16.shape[1]
         self.inv_lambda = inv_lambda
         self.l1_packed = pack_lowrank_down(L1_bf16, inv_lambda) if self.r else None
         self.L2 = L2_bf16 if self.r else None
-        self.w_packed = {"e3m2": pack_weight_e3m2, "nibble": pack_weight, "mxfp4": pack_weight_mxfp4}[container](qw, sw)
+        if container == "e3m2" and resident == "w4":
+            self.qw, self.sw, self.w_packed = qw, sw, None
+        else:
+            self.w_packed = {"e3m2": pack_weight_e3m2, "nibble": pack_weight, "mxfp4": pack_weight_mxfp4}[container](qw, sw)
         self.bias = bias
         self._bufs = None
+
+    def weights(self):
+        """The packed weights the GEMM takes: resident, or expanded now from the resident 4-bit form."""
+        if self.w_packed is not None:
+            return self.w_packed
+        return pack_weight_e3m2(self.qw, self.sw, out=_staging_buffer(packed_weight_e3m2_bytes(self.N, self.K), self.qw.device))
 
     def buffers(self, M, device):
         if self._bufs is None or self._bufs[3].shape[0] != M:
@@ -532,7 +555,7 @@ class W4A4Linear:
     def gemm(self, qx, sx, h):
         if self.container == "e3m2":
             y = self.buffers(qx.M, qx.buf.device)[3]
-            return linear_w4a4_e3m2(qx, self.w_packed, self.N, h, self.L2, self.bias, out=y)
+            return linear_w4a4_e3m2(qx, self.weights(), self.N, h, self.L2, self.bias, out=y)
         y = self.buffers(qx.shape[1], qx.device)[3]
         fn = linear_w4a4 if self.container == "nibble" else linear_mxfp4
         return fn(qx, sx, self.w_packed, self.N, h, self.L2, self.bias, out=y)

@@ -229,3 +229,24 @@ def test_resident_layer_object(svdq, oracle, container):
     torch.cuda.synchronize()
     assert y2.shape == (70, N) and torch.equal(y2, lin.forward(dev(x[:70]), 0.9))
     assert rel_fro(synth.bf16_bits_to_f32(host_bits(y2)).astype(np.float64), orc["y64"][:70]) <= 2e-3
+
+
+def test_layers_with_resident_4bit_weights_share_one_staging_buffer(svdq, oracle):
+    """The default residency of the E3M2 execution: every layer keeps the canonical 4-bit weights and expands them
+    into ONE staging buffer right before its GEMM.  Two layers of different shapes used alternately give exactly the
+    outputs of the same layers with their expanded weights resident."""
+    layers = []
+    for seed, (M, K, N, r) in enumerate([(150, 512, 256, 32), (150, 256, 384, 16)]):
+        x, L = small_layer(40 + seed, M, K, N, r)
+        args = (dev(L.inv_lambda), dev(L.L1), dev(L.L2), dev(L.qw), dev(L.sw), dev(L.bias))
+        layers.append((dev(x), svdq.W4A4Linear(*args), svdq.W4A4Linear(*args, resident="packed")))
+    assert layers[0][1].w_packed is None and layers[0][2].w_packed is not None
+    for rep in range(2):
+        for xd, w4, packed in layers:
+            y = w4.forward(xd, 0.8).clone()
+            assert torch.equal(y, packed.forward(xd, 0.8))
+    torch.cuda.synchronize()
+    from paper_2605_27003_amd import binding
+    assert len(binding._staging) == 1
+    (buf,) = binding._staging.values()
+    assert buf.numel() == max(svdq.packed_weight_e3m2_bytes(256, 512), svdq.packed_weight_e3m2_bytes(384, 256))
