@@ -14,10 +14,13 @@ namespace svdq {
 // ALL global loads are issued before the first use: the code path is the same for r = 16 and r = 32 (the second
 // k-step then reads valid addresses and its L2 fragment is zeroed), so their latency is paid once, not per
 // k-step.  Rows beyond M are clamped for the loads (their results are never stored).
-template <int NI, int MT>
-__device__ __forceinline__ void add_lowrank_bias(float16v (&y)[NI][MT], const float* __restrict__ h,
-                                                 const uint16_t* __restrict__ L2, const float* __restrict__ bias,
-                                                 int64_t m0, int n0, int64_t M, int N, int r, int lane) {
+//
+// h_piece(mi, k) returns the four values h[token of block mi][k .. k + 3] of this lane's token (k a multiple of 4):
+// from global memory in add_lowrank_bias, from wherever the caller staged the tile's h rows in add_lowrank_bias_from.
+template <int NI, int MT, class HPiece>
+__device__ __forceinline__ void add_lowrank_bias_from(float16v (&y)[NI][MT], HPiece h_piece,
+                                                      const uint16_t* __restrict__ L2, const float* __restrict__ bias,
+                                                      int n0, int N, int r, int lane) {
     const int l32 = lane & 31, kh = lane >> 5;
     float4 bv[NI][4];
 #pragma unroll
@@ -45,11 +48,8 @@ __device__ __forceinline__ void add_lowrank_bias(float16v (&y)[NI][MT], const fl
             }
 #pragma unroll
             for (int mi = 0; mi < MT; ++mi) {
-                int64_t m = m0 + mi * 32 + l32;
-                if (m >= M) m = M - 1;
-                const float4* ph = reinterpret_cast<const float4*>(h + m * r + k0 + 8 * kh);
-                hv[ks][mi][0] = ph[0];
-                hv[ks][mi][1] = ph[1];
+                hv[ks][mi][0] = h_piece(mi, k0 + 8 * kh);
+                hv[ks][mi][1] = h_piece(mi, k0 + 8 * kh + 4);
             }
         }
 #pragma unroll
@@ -95,6 +95,18 @@ __device__ __forceinline__ void add_lowrank_bias(float16v (&y)[NI][MT], const fl
                 y[ni][mi][4 * q + 2] += bv[ni][q].z;
                 y[ni][mi][4 * q + 3] += bv[ni][q].w;
             }
+}
+
+template <int NI, int MT>
+__device__ __forceinline__ void add_lowrank_bias(float16v (&y)[NI][MT], const float* __restrict__ h,
+                                                 const uint16_t* __restrict__ L2, const float* __restrict__ bias,
+                                                 int64_t m0, int n0, int64_t M, int N, int r, int lane) {
+    const int l32 = lane & 31;
+    add_lowrank_bias_from<NI, MT>(y, [&](const int mi, const int k) {
+        int64_t m = m0 + mi * 32 + l32;
+        if (m >= M) m = M - 1;
+        return *reinterpret_cast<const float4*>(h + m * r + k);
+    }, L2, bias, n0, N, r, lane);
 }
 
 // The binary32 output (test path): a lane stores 4 consecutive channels of its token per register quad.

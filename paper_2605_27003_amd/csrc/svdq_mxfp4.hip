@@ -653,6 +653,15 @@ void gemm_mx_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__
 // loop and the store, and the store transposes through its own LDS area behind a three-slot ring.  Tiles are taken
 // in the same XCD-aware order (tile ids b, b + gridDim, ...; gridDim a multiple of 8 keeps a block on one XCD's
 // share).  Same arithmetic, same order of operations per output as gemm_mx_kernel.
+//
+// The low-rank term's h rows (eq. 7: 256 tokens x r binary32 per tile) were what a tile start waited for longest:
+// sixteen 16-byte loads per lane, requested behind the previous tile's stores (measured: 6-7 % of the kernel at
+// K = 5120).  They now travel like the operands: the first two stages of a tile request the NEXT tile's rows into an
+// LDS area of their own, in the instruction slots of the second group that carry no operand request, and the tile
+// start reads them from there.  A token has eight 16-byte places there (128 bytes, r = 32; with r = 16 the upper four
+// hold nothing of use); piece c of token t sits at place c ^ ((t >> 1) & (r / 4 - 1)): a lane reads one piece of its
+// own token, and with the pieces rotated by token the 32 tokens of an instruction spread over the banks.  To make
+// room the store transposes one 32 x 32 accumulator block at a time (rows of 64 bytes, padded to 80).
 template <int MT>
 __global__ __launch_bounds__(512, 1)
 void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* __restrict__ sxe,
@@ -663,17 +672,22 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
     constexpr int WNC = 4;
     using G = MxGeom<MT, WNC>;
     constexpr int BM = G::BM, NDMA = G::NDMA, NS = 3;
-    constexpr uint32_t STORE_ROWS = 32;                               // the store goes through LDS 32 tokens at a time
-    __shared__ __attribute__((aligned(16))) uint8_t ring[NS * G::STAGE + 2 * WNC * STORE_ROWS * YROW];
+    constexpr uint32_t YROW32 = 80;                                   // 32 channels of a token as bf16 + 16 bytes of padding
+    constexpr uint32_t STORE_BYTES = 32 * YROW32;                     // per wave: one 32-token x 32-channel block at a time
+    constexpr uint32_t HBUF = (uint32_t)BM * 128;                     // the tile's h rows, r <= 32
+    __shared__ __attribute__((aligned(16))) uint8_t ring[NS * G::STAGE + 2 * WNC * STORE_BYTES + HBUF];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 1, wn = wave >> 1;
     const int l32 = lane & 31, kh = lane >> 5;
     const int ng = K >> 6;
-    const int nstages = (ng + 1) >> 1;                                // >= NS + 1 (the launcher sees to it)
+    const int nstages = (ng + 1) >> 1;                                // >= NS + 2 (the launcher sees to it)
     const uint32_t ring0 = (uint32_t)(uintptr_t)(lds_byte*)ring;
-    const uint32_t store0 = ring0 + NS * G::STAGE + wave * STORE_ROWS * YROW;
+    const uint32_t store0 = ring0 + NS * G::STAGE + wave * STORE_BYTES;
+    const uint32_t hbuf0 = ring0 + NS * G::STAGE + 2 * WNC * STORE_BYTES;
+    const int ptm = (r >> 2) - 1;                                     // 16-byte pieces per token of h, less one; r is 0, 16 or 32
+    constexpr int H_TRANSFERS = 4;                                    // 1-KB transfers per wave and tile: BM x 128 bytes over 8 waves
 
     // tile ids: the one-tile kernel's order (svdq_tiles.h), of which this block takes ids b, b + gridDim, ...
     const int total = tile_ids(tg);
@@ -729,6 +743,20 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
 #pragma unroll
         for (int p = 0; p < NDMA; ++p) stage_piece(t, s, slot, p);
     };
+    // transfer i (0 .. H_TRANSFERS - 1) of this wave for the h rows of the tile whose first token is m0: eight tokens,
+    // lane l fills place l % 8 of token l / 8 (a place that holds nothing of use re-reads a piece that exists).  No
+    // branch: a stage must stay one basic block, or the compiler moves its matrix instructions out of their places.
+    // With r = 0 the launcher passes some readable address as h, and the lanes read within its first 128 bytes.
+    auto h_request = [&](const int64_t m0, const int i) {
+        int ln = lane;
+        asm volatile("" : "+v"(ln));                                  // the address arithmetic stays where the request is
+        const int j = wave * H_TRANSFERS + i;
+        const int t = j * 8 + (ln >> 3);
+        const int c = ((ln & 7) ^ (t >> 1)) & ptm & 7;
+        const int64_t left = M - 1 - m0;                              // rows beyond M: the last row again
+        const int row = (t < left) ? t : (int)left;
+        dma16(h + m0 * r, (uint32_t)(row * r * 4 + c * 16), hbuf0 + j * 1024);
+    };
 
     const uint32_t rd_a = G::OFF_A + (kh * BM + wm * (32 * MT) + l32) * 16;
     const uint32_t rd_w = G::OFF_W + (wn * 2 * 64 + lane) * 16;
@@ -776,11 +804,15 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
     TileAddr T = tile_addr(id);
     uint32_t cur = ring0;                                             // slot of the current tile's stage 0
     {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) h_request(T.m0, i);         // the first tile's h rows: requested first, awaited below
         uint32_t sl = cur;
         for (int s = 0; s < NS; ++s) {
             stage_issue(T, s, sl);
             sl = next_slot(sl);
         }
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NS * NDMA) : "memory");
+        __syncthreads();
     }
 
     // What a stage does once its first group is multiplied: the stage after it (of this tile or of the next) is awaited
@@ -802,9 +834,16 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
             for (int b = 0; b < MT; ++b)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) y[a][b][i] = 0.0f;
-        // y starts as the low-rank term plus the bias (eq. 7, 11); its loads return behind the transfers already
-        // requested for this tile, which were requested a stage or more ago
-        add_lowrank_bias<2, MT>(y, h, L2, bias, mw, T.n0 + wn * 64, M, N, r, lane_t);
+        // y starts as the low-rank term plus the bias (eq. 7, 11).  The tile's h rows are in LDS: requested during the
+        // previous tile's first stages (by every wave, each of which has since waited for younger transfers and passed
+        // barriers), or before the loop for the block's first tile.
+        const int th = wm * (32 * MT) + (lane_t & 31);               // this lane's token of block 0; the rotation is the same for
+        const int rot = (th >> 1) & ptm;                             // all its blocks (32 tokens apart)
+        const uint32_t hrow = hbuf0 + th * 128;
+        add_lowrank_bias_from<2, MT>(y, [&](const int mi, const int k) {
+            const uint4 v = lds_read16(hrow + (((k >> 2) ^ rot) << 4) + mi * (32 * 128));
+            return float4{__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+        }, L2, bias, T.n0 + wn * 64, N, r, lane_t);
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * NDMA) : "memory");    // stage 0 of this tile
         __syncthreads();
         fetch(op0, cur, 0);
@@ -821,7 +860,7 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
                 const int8v b = {(int)o.xf[mi].x, (int)o.xf[mi].y, (int)o.xf[mi].z, (int)o.xf[mi].w, 0, 0, 0, 0};
                 y[ni][mi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, y[ni][mi], 4, 4, j, (int)o.sw[ni], j, (int)o.sx[mi]);
                 __builtin_amdgcn_sched_barrier(0);
-                if (t < NDMA) request(t);
+                request(t);
                 if (doit) {
                     if (t < 2) {
                         on.wf[t] = lds_read16_pinned(slot + rd_w + jn * 2048 * WNC + t * 1024);
@@ -840,47 +879,81 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
         // Between the two groups of a stage stand only the wait and the barrier: the stage after this one is awaited
         // and made visible, and this stage's slot is free (every read of it was requested during the first group).
         // The second group's instructions then also carry the slot's new transfer requests, one each.
-        auto stage_body = [&](const int s, const uint32_t c, const uint32_t nxt, auto SAMEC, auto ENDC) {
+        // HC >= 0: the instructions left over also request transfers HC, HC + 1, ... of the NEXT tile's h rows.  These
+        // are younger than the operand transfers the waits count, so every wait holds for at least what it names.
+        auto stage_body = [&](const int s, const uint32_t c, const uint32_t nxt, auto SAMEC, auto ENDC, auto HCC) {
             constexpr bool SAME = decltype(SAMEC)::value, END = decltype(ENDC)::value;
+            constexpr int HC = decltype(HCC)::value;
             mma_with_fetch(op0, IC<0>{}, op1, c, 1, true, [](int) {});
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NDMA) : "memory");
             __syncthreads();
             mma_with_fetch(op1, IC<1>{}, op0, nxt, 0, !END, [&](const int p) {
-                if (SAME) stage_piece(T, s + NS, c, p);
+                if (p >= NDMA) {
+                    if (HC >= 0) h_request(T1.m0, HC + p - NDMA);
+                } else if (SAME) stage_piece(T, s + NS, c, p);
                 else stage_piece(T1, s + NS - nstages, c, p);
             });
         };
         int s = 0;
+        {
+            static_assert(NDMA == 5, "three free instructions per stage: the four h transfers take two stages");
+            uint32_t nxt = next_slot(cur);
+            stage_body(0, cur, nxt, IC<1>{}, IC<0>{}, IC<0>{});
+            cur = nxt;
+            nxt = next_slot(cur);
+            stage_body(1, cur, nxt, IC<1>{}, IC<0>{}, IC<3>{});
+            cur = nxt;
+            s = 2;
+        }
         for (; s + NS < nstages; ++s) {
             const uint32_t nxt = next_slot(cur);
-            stage_body(s, cur, nxt, IC<1>{}, IC<0>{});
+            stage_body(s, cur, nxt, IC<1>{}, IC<0>{}, IC<-1>{});
             cur = nxt;
         }
         for (; s + 1 < nstages; ++s) {
             const uint32_t nxt = next_slot(cur);
-            stage_body(s, cur, nxt, IC<0>{}, IC<0>{});
+            stage_body(s, cur, nxt, IC<0>{}, IC<0>{}, IC<-1>{});
             cur = nxt;
         }
-        stage_body(s, cur, next_slot(cur), IC<0>{}, IC<1>{});
+        stage_body(s, cur, next_slot(cur), IC<0>{}, IC<1>{}, IC<-1>{});
         cur = next_slot(cur);                                         // where the next tile's stage 0 went
 
         // ---- store: the ring belongs to the next tile by now, so the transposition uses the area behind it.  (The
         // emitting epilogues stay with the four-wave kernel: alone on its CU a block would run their vector-ALU work,
         // about 10 k clocks per tile, beside nothing; measured 1.83 ms against 1.58 ms for the C3 up-projection.)
+        int lane_s = lane;
+        asm volatile("" : "+v"(lane_s));                              // the store's address arithmetic stays behind the K loop
         if (out_f32) {
-            store_tile_f32<2, MT>(y, reinterpret_cast<float*>(yout), ldy, mw, T.n0 + wn * 64, M, lane_t);
+            store_tile_f32<2, MT>(y, reinterpret_cast<float*>(yout), ldy, mw, T.n0 + wn * 64, M, lane_s);
         } else {
             uint16_t* yw = reinterpret_cast<uint16_t*>(yout) + mw * ldy + T.n0 + wn * 64;
-            auto store_chunk = [&](auto CC) {                          // 32 tokens: accumulator block c of both n-blocks
-                constexpr int c = decltype(CC)::value;
-                store_tile_bf16<1>([&](int ni, int mi, int i) { return y[ni][c + mi][i]; },
-                                   store0, lane_t, yw + (int64_t)(32 * c) * ldy, ldy, M - mw - 32 * c);
+            // one accumulator block (32 tokens x 32 channels) at a time through this wave's LDS region: a lane writes
+            // its token's 4-channel pieces, then four lanes store a token's 64 bytes
+            auto store_block = [&](auto CC, auto NIC) {
+                constexpr int c = decltype(CC)::value, ni = decltype(NIC)::value;
+                const int l32s = lane_s & 31, khs = lane_s >> 5;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint2 o = {f2_bf16_rne(y[ni][c][4 * q + 0], y[ni][c][4 * q + 1]),
+                                     f2_bf16_rne(y[ni][c][4 * q + 2], y[ni][c][4 * q + 3])};
+                    lds_write8_pinned(store0 + l32s * YROW32 + (8 * q + 4 * khs) * 2, o);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const int rsub = lane_s >> 2, c16 = lane_s & 3;
+                const int64_t rows_left = M - mw - 32 * c;
+#pragma unroll
+                for (int it = 0; it < 2; ++it) {
+                    const int row = it * 16 + rsub;
+                    const uint4 v = lds_read16_pinned(store0 + row * YROW32 + c16 * 16);
+                    if (row < rows_left) *reinterpret_cast<uint4*>(yw + (int64_t)(32 * c + row) * ldy + ni * 32 + c16 * 8) = v;
+                }
             };
             static_assert(MT == 4, "four 32-token chunks");
-            store_chunk(IC<0>{});
-            store_chunk(IC<1>{});
-            store_chunk(IC<2>{});
-            store_chunk(IC<3>{});
+            store_block(IC<0>{}, IC<0>{}); store_block(IC<0>{}, IC<1>{});
+            store_block(IC<1>{}, IC<0>{}); store_block(IC<1>{}, IC<1>{});
+            store_block(IC<2>{}, IC<0>{}); store_block(IC<2>{}, IC<1>{});
+            store_block(IC<3>{}, IC<0>{}); store_block(IC<3>{}, IC<1>{});
         }
         if (nid < 0) break;
         id = nid;
@@ -935,11 +1008,11 @@ static int cu_count() {
 }
 
 // the tile-walking kernel runs one block per CU (a multiple of 8 blocks, so that a block stays on one XCD's share of
-// the tile order); it needs full 256-channel tiles, a K loop longer than its ring, and pays once every block has at
-// least two tiles
+// the tile order); it needs full 256-channel tiles, a K loop of at least five stages (two more than its ring), and
+// pays once every block has at least two tiles
 static inline int walking_blocks() { return cu_count() / 8 * 8; }
 static inline bool walks_tiles(int mtiles, int N, int K) {
-    return N % 256 == 0 && K >= 512 && (int64_t)mtiles * (N / 256) >= 2 * walking_blocks();
+    return N % 256 == 0 && K >= 576 && (int64_t)mtiles * (N / 256) >= 2 * walking_blocks();
 }
 
 hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w_packed,
@@ -951,8 +1024,10 @@ hipError_t launch_linear_mx(const uint8_t* qx, const uint8_t* sxe, const void* w
     const uint16_t* wsc = (const uint16_t*)(base + mx_wfrag_bytes(N, K));
     const int mtiles = (int)((M + 64 * MT - 1) / (64 * MT));
     if (walks_tiles(mtiles, N, K)) {         // 256 x 256 block tiles, eight waves, one block per CU walking its tiles
+        // without a low-rank branch the kernel's h transfers still run (they have no branch): give them the codes to read
+        const float* hrows = (r > 0) ? h : (const float*)qx;
         hipLaunchKernelGGL((gemm_mx_persistent_kernel<MT>), dim3((unsigned)walking_blocks()), dim3(512), 0, stream,
-                           qx, (const uint16_t*)sxe, (const uint4*)base, wsc, h, (const uint16_t*)L2, bias,
+                           qx, (const uint16_t*)sxe, (const uint4*)base, wsc, hrows, (const uint16_t*)L2, bias,
                            M, N, K, r, y, ldy, out_f32, make_tile_grid(mtiles, N / 256));
     } else if (N % 256 == 0) {               // 256 x 256 block tiles, eight waves, one block per CU and tile
         const TileGrid tg = make_tile_grid(mtiles, N / 256);

@@ -77,11 +77,12 @@ def test_ragged_shapes(svdq, oracle, M, K, N, r):
     run_layer(svdq, oracle, x, L, 0.8, f"M={M} K={K} N={N} r={r}")
 
 
-@pytest.mark.parametrize("M,K,N,r", [(1999, 512, 16384, 32), (2050, 1088, 16384, 16), (4100, 576, 8192, 0)])
+@pytest.mark.parametrize("M,K,N,r", [(1999, 640, 16384, 32), (2050, 1088, 16384, 16), (4100, 576, 8192, 0),
+                                      (1999, 512, 16384, 32)])
 def test_tile_walking_kernel_shapes(svdq, oracle, M, K, N, r):
-    """Shapes with at least 512 tiles of 256 x 256 and K >= 512: the GEMM then runs as one block per CU that walks
-    its tiles.  Ragged last token tile, an odd group count, three to nine stages per tile, with and without the
-    low-rank branch."""
+    """Shapes with at least 512 tiles of 256 x 256 and K >= 576: the GEMM then runs as one block per CU that walks
+    its tiles and stages each next tile's low-rank input in LDS.  Ragged last token tile, an odd group count, five
+    to nine stages per tile, r = 32, 16 and none; the last shape (four stages) stays with one block per tile."""
     x, L = small_layer(11, M, K, N, r)
     run_layer(svdq, oracle, x, L, 0.8, f"tile-walking M={M} K={K} N={N} r={r}")
 
