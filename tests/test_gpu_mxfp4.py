@@ -87,6 +87,23 @@ def test_tile_walking_kernel_shapes(svdq, oracle, M, K, N, r):
     run_layer(svdq, oracle, x, L, 0.8, f"tile-walking M={M} K={K} N={N} r={r}")
 
 
+def test_tile_walking_kernel_without_bias(svdq, oracle):
+    """The tile-walking GEMM with a low-rank branch and no bias, and with neither: its h transfers then read a
+    substitute address and must leave the result alone."""
+    M, K, N = 1100, 704, 32768
+    for r in (32, 0):
+        x, L = small_layer(13, M, K, N, r)
+        DL = MxLayer(svdq, L)
+        qx, sx, h = svdq.quantize_act_mxfp4(dev(x), DL.inv_lambda, 0.8, DL.l1p, r)
+        y = svdq.linear_mxfp4(qx, sx, DL.wp, N, h, DL.L2 if r else None, None)
+        y32 = svdq.linear_mxfp4(qx, sx, DL.wp, N, h, DL.L2 if r else None, None, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        oq, os_ = oracle.quantize_act_mxfp4(x, L.inv_lambda, 0.8)
+        oh = oracle.lowrank_down(x, L.inv_lambda, L.L1) if r else None
+        orc = oracle.linear_mxfp4(oq, os_, L.qw, L.sw, oh, L.L2 if r else None, None)
+        check_y(host_bits(y), y32.cpu().numpy(), orc, f"tile-walking, no bias, r={r}")
+
+
 def test_degenerate_blocks_and_ties(svdq, oracle):
     """All-zero rows and blocks, blocks below the scale range, the hand-worked tie vectors, saturation."""
     M, K, N, r = 40, 256, 128, 16
