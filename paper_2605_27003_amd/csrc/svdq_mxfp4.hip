@@ -927,33 +927,43 @@ void gemm_mx_persistent_kernel(const uint8_t* __restrict__ qx, const uint16_t* _
             store_tile_f32<2, MT>(y, reinterpret_cast<float*>(yout), ldy, mw, T.n0 + wn * 64, M, lane_s);
         } else {
             uint16_t* yw = reinterpret_cast<uint16_t*>(yout) + mw * ldy + T.n0 + wn * 64;
-            // one accumulator block (32 tokens x 32 channels) at a time through this wave's LDS region: a lane writes
-            // its token's 4-channel pieces, then four lanes store a token's 64 bytes
-            auto store_block = [&](auto CC, auto NIC) {
+            // One accumulator block (32 tokens x 32 channels) at a time through this wave's LDS region: a lane writes its
+            // token's 4-channel pieces, then four lanes store a token's 64 bytes.  Software-pipelined: a block's two
+            // reads are requested together, and the NEXT block is converted and written behind them, before the wait
+            // for their data -- LDS serves a wave's requests in order, so the reads see the old block and the writes
+            // land after them.  (One read, wait, store at a time, the 32 LDS round trips were the whole store phase.)
+            const int l32s = lane_s & 31, khs = lane_s >> 5;
+            const uint32_t wr0 = store0 + l32s * YROW32 + 8 * khs;
+            const int rsub = lane_s >> 2, c16 = lane_s & 3;
+            const uint32_t rd0 = store0 + rsub * YROW32 + c16 * 16;
+            uint16_t* const yl = yw + (int64_t)rsub * ldy + c16 * 8;
+            const int64_t rows_left = M - mw - rsub;                   // this lane stores rows rsub + 16 it + 32 c
+            auto cvt_write = [&](auto CC, auto NIC) {
                 constexpr int c = decltype(CC)::value, ni = decltype(NIC)::value;
-                const int l32s = lane_s & 31, khs = lane_s >> 5;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const uint2 o = {f2_bf16_rne(y[ni][c][4 * q + 0], y[ni][c][4 * q + 1]),
                                      f2_bf16_rne(y[ni][c][4 * q + 2], y[ni][c][4 * q + 3])};
-                    lds_write8_pinned(store0 + l32s * YROW32 + (8 * q + 4 * khs) * 2, o);
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                const int rsub = lane_s >> 2, c16 = lane_s & 3;
-                const int64_t rows_left = M - mw - 32 * c;
-#pragma unroll
-                for (int it = 0; it < 2; ++it) {
-                    const int row = it * 16 + rsub;
-                    const uint4 v = lds_read16_pinned(store0 + row * YROW32 + c16 * 16);
-                    if (row < rows_left) *reinterpret_cast<uint4*>(yw + (int64_t)(32 * c + row) * ldy + ni * 32 + c16 * 8) = v;
+                    lds_write8_pinned(wr0 + 16 * q, o);
                 }
             };
+            auto read_store = [&](auto CC, auto NIC, auto next) {
+                constexpr int c = decltype(CC)::value, ni = decltype(NIC)::value;
+                const uint4 v0 = lds_read16_pinned(rd0), v1 = lds_read16_pinned(rd0 + 16 * YROW32);
+                next();
+                if (32 * c < rows_left) *reinterpret_cast<uint4*>(yl + (int64_t)(32 * c) * ldy + ni * 32) = v0;
+                if (32 * c + 16 < rows_left) *reinterpret_cast<uint4*>(yl + (int64_t)(32 * c + 16) * ldy + ni * 32) = v1;
+            };
             static_assert(MT == 4, "four 32-token chunks");
-            store_block(IC<0>{}, IC<0>{}); store_block(IC<0>{}, IC<1>{});
-            store_block(IC<1>{}, IC<0>{}); store_block(IC<1>{}, IC<1>{});
-            store_block(IC<2>{}, IC<0>{}); store_block(IC<2>{}, IC<1>{});
-            store_block(IC<3>{}, IC<0>{}); store_block(IC<3>{}, IC<1>{});
+            cvt_write(IC<0>{}, IC<0>{});
+            read_store(IC<0>{}, IC<0>{}, [&] { cvt_write(IC<0>{}, IC<1>{}); });
+            read_store(IC<0>{}, IC<1>{}, [&] { cvt_write(IC<1>{}, IC<0>{}); });
+            read_store(IC<1>{}, IC<0>{}, [&] { cvt_write(IC<1>{}, IC<1>{}); });
+            read_store(IC<1>{}, IC<1>{}, [&] { cvt_write(IC<2>{}, IC<0>{}); });
+            read_store(IC<2>{}, IC<0>{}, [&] { cvt_write(IC<2>{}, IC<1>{}); });
+            read_store(IC<2>{}, IC<1>{}, [&] { cvt_write(IC<3>{}, IC<0>{}); });
+            read_store(IC<3>{}, IC<0>{}, [&] { cvt_write(IC<3>{}, IC<1>{}); });
+            read_store(IC<3>{}, IC<1>{}, [] {});
         }
         if (nid < 0) break;
         id = nid;
